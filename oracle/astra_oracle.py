@@ -1,0 +1,311 @@
+"""CPU oracle for the classifier-layer hot path of ASTRA (arXiv 2409.20156).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition of what
+the GPU library must compute.  Only the test-suite, the smoke check and the
+`cpu_baseline` leg of the benchmark may import it.  It shares no code with the
+HIP path and never imports it.  Everything is numpy in float64; pure Python
+integers are used where 128-bit products are needed.
+
+Functions and the passage of the paper each one follows
+-------------------------------------------------------
+mine_negatives      Alg. 1 "ANNS refresh" step, realised as exact search (the
+                    paper's own control experiment, Sec. 5.2.1(a)): ids of the
+                    k_h labels with the largest <w_l, z_i> (Sec. 2.1 score).
+sample_negatives    Alg. 1 hard+random step and Sec. 3.1 Idea 2: all k_h stale
+                    hard negatives plus k_r i.i.d. uniform draws from
+                    [L] \\ H_i, p = 1/(L-k_h) as under Eq. 2.  Warm-up mode
+                    (Alg. 1, t < tau_s): all negatives uniform on [L].
+xc_step             Eq. 2 (sampled BCE) with its analytic gradient (form given
+                    in the proof of Lemma 1) and the mini-batch SGD update of
+                    W from Alg. 1; loss averaged over data points (Sec. 4).
+                    A soft-max variant with proposal-corrected logits is the
+                    second loss kind.
+full_bce_loss       Eq. 1, every one of the L labels, for pinning Eq. 2.
+full_softmax_loss   plain soft-max cross-entropy over all L labels.
+
+Readings of the paper taken here (each is listed in the design document):
+labels are 0..L-1 and W is stored L x d; random negatives are drawn with
+replacement; positives are not excluded from the draw but get weight zero
+through the (1 - y_l) factor; ids outside [0, L) are padding.
+
+Parity status: every function below is pinned by tests that do not re-use its
+own formula (closed forms, brute force over all labels through a library BCE,
+Monte-Carlo unbiasedness of Eq. 2 against Eq. 1, finite differences, exhaustive
+enumeration of the complement map, published splitmix64 vectors).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+LOSS_BCE = 0
+LOSS_SOFTMAX = 1
+
+_MASK64 = (1 << 64) - 1
+_K_QUERY = 0x9E3779B97F4A7C15   # odd constant separating query streams
+_K_DRAW = 0xD1B54A32D192ED03    # odd constant separating draws of one query
+
+
+# --------------------------------------------------------------------------
+# storage rounding
+# --------------------------------------------------------------------------
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round float64 values to the nearest bfloat16 value (ties to even),
+    returned as float64.  bfloat16 keeps 8 significant bits, so the spacing of
+    representable numbers around x = m * 2**e (0.5 <= |m| < 1) is 2**(e-8)."""
+    x = np.asarray(x, dtype=np.float64)
+    _, e = np.frexp(x)
+    e = np.maximum(e, -125)                     # below that bf16 is subnormal
+    q = np.ldexp(1.0, e - 8)
+    return np.rint(x / q) * q                   # rint rounds half to even
+
+
+def round_to_f32(x: np.ndarray) -> np.ndarray:
+    return np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+
+def _round_storage(x, dtype: str):
+    if dtype == "bf16":
+        return round_to_bf16(x)
+    if dtype == "f32":
+        return round_to_f32(x)
+    if dtype == "f64":
+        return np.asarray(x, dtype=np.float64)
+    raise ValueError(dtype)
+
+
+# --------------------------------------------------------------------------
+# S1  mining: exact top-k inner product
+# --------------------------------------------------------------------------
+def mine_negatives(Z, W, k_h: int, chunk: int = 1 << 16):
+    """For every query row z_i return the ids of the k_h rows of W with the
+    largest inner product, best first; equal scores are ordered by smaller id.
+    Returns (ids int32 [Zq,k_h], scores float64 [Zq,k_h]).
+
+    Definition written out: all L scores, then a full ordering.  `chunk` only
+    bounds the size of the temporary score block; the block results are
+    concatenated candidates that are ordered again, so nothing is approximated.
+    """
+    Z = np.asarray(Z, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    Zq, d = Z.shape
+    L, d2 = W.shape
+    assert d == d2 and 1 <= k_h <= L
+    cand_s = np.empty((Zq, 0), dtype=np.float64)
+    cand_i = np.empty((Zq, 0), dtype=np.int64)
+    for l0 in range(0, L, chunk):
+        l1 = min(L, l0 + chunk)
+        S = Z @ W[l0:l1].T                                  # [Zq, l1-l0]
+        ids = np.broadcast_to(np.arange(l0, l1, dtype=np.int64), S.shape)
+        s_all = np.concatenate([cand_s, S], axis=1)
+        i_all = np.concatenate([cand_i, ids], axis=1)
+        # order each row by (score descending, id ascending)
+        order = np.lexsort((i_all, -s_all), axis=1)[:, :k_h]
+        cand_s = np.take_along_axis(s_all, order, axis=1)
+        cand_i = np.take_along_axis(i_all, order, axis=1)
+    return cand_i.astype(np.int32), cand_s
+
+
+# --------------------------------------------------------------------------
+# S2  sampling
+# --------------------------------------------------------------------------
+def _fmix64(x: int) -> int:
+    """Finaliser of the splitmix64 generator (Steele, Lea, Flood 2014)."""
+    x &= _MASK64
+    x ^= x >> 30
+    x = (x * 0xBF58476D1CE4E5B9) & _MASK64
+    x ^= x >> 27
+    x = (x * 0x94D049BB133111EB) & _MASK64
+    x ^= x >> 31
+    return x
+
+
+def draw_u64(seed: int, i: int, j: int) -> int:
+    """Counter-based 64-bit word for query i, draw j: a function of the three
+    integers only, so any thread layout reproduces it."""
+    a = _fmix64((seed & _MASK64) ^ ((_K_QUERY * (i + 1)) & _MASK64))
+    return _fmix64((a + _K_DRAW * (j + 1)) & _MASK64)
+
+
+def bounded(u: int, m: int) -> int:
+    """Map a 64-bit word to [0, m) by the high half of the 128-bit product."""
+    return (u * m) >> 64
+
+
+def complement_select(hs_sorted, r: int) -> int:
+    """r-th smallest (0-based) element of {0,1,2,...} \\ hs_sorted.
+    hs_sorted is strictly increasing.  With c = #{m : hs[m] - m <= r} the
+    answer is r + c: exactly c excluded ids lie below it."""
+    c = 0
+    for m, h in enumerate(hs_sorted):
+        if h - m <= r:
+            c += 1
+    return r + c
+
+
+def sample_negatives(shortlist, B: int, k_h: int, k_r: int, L: int, seed: int):
+    """Negatives and log-proposal for one mini-batch.
+
+    shortlist: int [B, k_h] (row i = stale hard negatives of query i) or None
+    for the warm-up phase.  Returns (neg int32 [B, k_h+k_r], logq float32).
+
+    Hard mode: slots 0..k_h-1 are the shortlist row verbatim with logq = 0
+    (taken with probability one, weight 1 in Eq. 2).  Slots k_h.. hold k_r
+    i.i.d. uniform draws from [L] \\ H_i, where H_i is the set of distinct
+    in-range ids of the row (size u_i, equal to k_h for a mined shortlist);
+    logq = log(k_r / (L - u_i)), the log of the expected number of copies of a
+    label among the draws, so that exp(-logq) = 1/(p k_r) of Eq. 2.
+    Warm-up mode: all k_h+k_r slots uniform on [L], logq = log((k_h+k_r)/L).
+    """
+    n = k_h + k_r
+    neg = np.empty((B, n), dtype=np.int32)
+    logq = np.empty((B, n), dtype=np.float32)
+    for i in range(B):
+        if shortlist is None:
+            hs = []
+            n_draw, first = n, 0
+        else:
+            row = [int(v) for v in shortlist[i][:k_h]]
+            neg[i, :k_h] = row
+            logq[i, :k_h] = 0.0
+            hs = sorted({v for v in row if 0 <= v < L})
+            n_draw, first = k_r, k_h
+        M = L - len(hs)
+        assert M >= 1
+        for j in range(n_draw):
+            r = bounded(draw_u64(seed, i, j), M)
+            neg[i, first + j] = complement_select(hs, r)
+        if n_draw:
+            logq[i, first:] = np.float32(np.log(np.float64(n_draw) / np.float64(M)))
+    return neg, logq
+
+
+# --------------------------------------------------------------------------
+# S3-S5  the sampled training step
+# --------------------------------------------------------------------------
+def _softplus(x):
+    """log(1 + exp(x)) without overflow."""
+    return np.maximum(x, 0.0) + np.log1p(np.exp(-np.abs(x)))
+
+
+def _sigmoid(x):
+    return np.where(x >= 0, 1.0 / (1.0 + np.exp(-np.abs(x))),
+                    np.exp(-np.abs(x)) / (1.0 + np.exp(-np.abs(x))))
+
+
+def _candidates(i, pos, neg, logq, L):
+    """Lists (label, is_positive, weight a, logq) of query i after masking:
+    out-of-range ids are padding; a negative that is one of the query's
+    positives carries the factor (1 - y_l) = 0 and is dropped."""
+    pset = [int(l) for l in pos[i] if 0 <= l < L]
+    out = [(l, True, 1.0, 0.0) for l in pset]
+    pmember = set(pset)
+    for j in range(neg.shape[1]):
+        l = int(neg[i, j])
+        if 0 <= l < L and l not in pmember:
+            lq = float(logq[i, j])
+            out.append((l, False, float(np.exp(-lq)), lq))
+    return out
+
+
+def xc_step(Z, W, pos, neg, logq, lr: float, kind: int = LOSS_BCE,
+            storage: str = "f64"):
+    """One classifier-layer step.  Inputs: Z [B,d], W [L,d] (values as stored;
+    not modified), pos int [B,k_p] (-1 padded), neg int [B,n], logq [B,n].
+
+    Returns dict with
+      loss     float64 scalar, mean over the B queries
+      dZ       float64 [B,d], gradient of `loss` w.r.t. Z (pre-update W)
+      touched  int32 ascending unique labels whose row changed
+      W_rows   float64 [len(touched), d] the updated rows, rounded to `storage`
+      coef     list per query of (label, dloss/dscore) for inspection
+
+    BCE kind (Eq. 2):  loss_i = sum_pos log(1+e^{-s}) + sum_neg a (s + log(1+e^{-s}))
+    with a = exp(-logq): 1 for hard, (L-k_h)/k_r = 1/(p k_r) for random.
+    d/ds: positives sigma(s)-1, negatives a sigma(s).
+    Soft-max kind: logits s - logq over the candidate set, loss_i = mean over
+    the positives of -log softmax; d/ds = softmax - [positive]/|pos_i|.
+    """
+    Z = np.asarray(Z, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    B, d = Z.shape
+    L = W.shape[0]
+    loss = 0.0
+    dZ = np.zeros((B, d))
+    dW = {}                                    # label -> gradient row
+    coef = []
+    for i in range(B):
+        cand = _candidates(i, pos, neg, logq, L)
+        labels = np.array([c[0] for c in cand], dtype=np.int64)
+        ispos = np.array([c[1] for c in cand], dtype=bool)
+        a = np.array([c[2] for c in cand])
+        lq = np.array([c[3] for c in cand])
+        if len(cand) == 0:
+            coef.append([])
+            continue
+        rows = W[labels]                       # [n_i, d]
+        s = rows @ Z[i]
+        if kind == LOSS_BCE:
+            li = np.where(ispos, _softplus(-s), a * _softplus(s))
+            g = np.where(ispos, _sigmoid(s) - 1.0, a * _sigmoid(s))
+            loss_i = li.sum()
+        elif kind == LOSS_SOFTMAX:
+            npos = int(ispos.sum())
+            if npos == 0:       # no positive: the query is skipped entirely
+                coef.append([])
+                continue
+            t = s - lq
+            m = t.max()
+            lse = m + np.log(np.exp(t - m).sum())
+            loss_i = -(t[ispos] - lse).sum() / npos
+            g = np.exp(t - lse) - ispos / npos
+        else:
+            raise ValueError(kind)
+        g = g / B                              # mean over the batch
+        loss += loss_i / B
+        dZ[i] = g @ rows
+        for l, gj in zip(labels, g):
+            dW.setdefault(int(l), np.zeros(d))
+            dW[int(l)] += gj * Z[i]
+        coef.append([(int(l), float(gj)) for l, gj in zip(labels, g)])
+    touched = np.array(sorted(dW.keys()), dtype=np.int32)
+    W_rows = np.empty((len(touched), d))
+    for r, l in enumerate(touched):
+        W_rows[r] = _round_storage(W[l] - lr * dW[int(l)], storage)
+    return {"loss": loss, "dZ": dZ, "touched": touched, "W_rows": W_rows,
+            "coef": coef, "dW": dW}
+
+
+# --------------------------------------------------------------------------
+# full-label references (tiny inputs only, O(B L d))
+# --------------------------------------------------------------------------
+def full_bce_loss(Z, W, pos):
+    """Eq. 1 averaged over the batch: every label is either a positive of the
+    query (first sum) or a negative (second sum)."""
+    Z = np.asarray(Z, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    B, L = Z.shape[0], W.shape[0]
+    total = 0.0
+    for i in range(B):
+        y = np.zeros(L)
+        for l in pos[i]:
+            if 0 <= l < L:
+                y[int(l)] = 1.0
+        s = W @ Z[i]
+        total += (y * _softplus(-s)).sum() + ((1.0 - y) * (s + _softplus(-s))).sum()
+    return total / B
+
+
+def full_softmax_loss(Z, W, pos):
+    """Soft-max cross-entropy over all L labels, averaged over the positives
+    of a query and over the batch."""
+    Z = np.asarray(Z, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    B, L = Z.shape[0], W.shape[0]
+    total = 0.0
+    for i in range(B):
+        p = [int(l) for l in pos[i] if 0 <= l < L]
+        s = W @ Z[i]
+        m = s.max()
+        lse = m + np.log(np.exp(s - m).sum())
+        total += -(s[p] - lse).sum() / len(p)
+    return total / B
