@@ -1,0 +1,127 @@
+/*
+ * astra_xc.h -- C ABI of the MI355X (gfx950) classifier-layer hot path of ASTRA
+ * (arXiv 2409.20156): hard-negative mining by exact top-k inner product, the
+ * hard+uniform negative mixture, and the sampled BCE training step with a sparse
+ * SGD update of the classifier rows.
+ *
+ * Conventions shared by every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing; temporary memory is a caller-provided workspace whose
+ *     size is asked for first (xc_*_workspace).  Workspaces and all arrays must
+ *     be 16-byte aligned.
+ *   - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast
+ *     to void*, NULL = the default stream).  No call synchronises; results,
+ *     including scalars, appear in device memory in stream order.
+ *   - W is row-major L x d (one label per contiguous row), Z row-major B x d,
+ *     both of type `t`.  Label ids are int32 in [0, L); any id outside that
+ *     range (-1 by convention) is padding and is ignored.
+ *   - Return value: XC_OK or a negative xc_status.  Shape and pointer errors are
+ *     detected on the host before anything is launched; nothing is written then.
+ *     After XC_EHIP, xc_last_hip_error() gives the hipError_t of this thread.
+ */
+#ifndef ASTRA_XC_H
+#define ASTRA_XC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { XC_F32 = 0, XC_BF16 = 1 } xc_dtype;            /* storage of Z and W; sums are fp32 */
+typedef enum { XC_LOSS_BCE = 0, XC_LOSS_SOFTMAX = 1 } xc_loss;
+
+typedef enum {
+    XC_OK = 0,
+    XC_EINVAL = -1,      /* null or misaligned pointer, bad enum value            */
+    XC_ESHAPE = -2,      /* unsupported or inconsistent sizes                     */
+    XC_EWORKSPACE = -3,  /* workspace smaller than xc_*_workspace reports         */
+    XC_EHIP = -4         /* a HIP runtime call failed; see xc_last_hip_error()    */
+} xc_status;
+
+/* limits checked by the host side of every call */
+#define XC_MAX_K_MINE 128      /* k_h accepted by xc_mine_negatives                */
+#define XC_MAX_K_SAMPLE 1024   /* k_h accepted by xc_sample_negatives              */
+#define XC_MAX_ROW_BYTES 4096  /* d * sizeof(element) accepted by xc_step          */
+#define XC_MAX_CANDIDATES 16384 /* k_p + n_neg accepted by xc_step                 */
+
+const char* xc_strerror(int status);
+int xc_last_hip_error(void);
+int xc_version(void);
+
+/* ---------------------------------------------------------------------------
+ * Mining (Alg. 1, the "ANNS refresh" step; Sec. 2.1 score f_l(x) = <w_l, z>).
+ * Exact search stands in for the ANNS index, which the paper itself ran as a
+ * control (Sec. 5.2.1 a).  For each of the Zq query rows of Z:
+ *   shortlist[i*k_h + r] = id of the label with the r-th largest <z_i, w_l>,
+ *   l in [0, L); equal scores are ordered by smaller id.
+ *   scores[i*k_h + r]    = that inner product (fp32), if scores != NULL.
+ * Products are accumulated in fp32.  The Zq x L score matrix is never stored.
+ * Requires 1 <= k_h <= min(L, XC_MAX_K_MINE), d*sizeof(element) a multiple of 16.
+ * A score that is NaN is never selected; a query with fewer than k_h finite
+ * scores gets id -1 and score -inf in the remaining slots.
+ * ------------------------------------------------------------------------- */
+int xc_mine_workspace(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, size_t* bytes);
+int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64_t L, int d, int k_h,
+                      xc_dtype t, int32_t* shortlist /* [Zq*k_h] out */,
+                      float* scores /* [Zq*k_h] out, or NULL */,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Negative sampling (Alg. 1, hard+random step; Sec. 3.1 Idea 2; p under Eq. 2).
+ * For query i of the batch, neg[i*(k_h+k_r) + ...]:
+ *   slots 0..k_h-1   the shortlist row of the query, copied verbatim, logq = 0
+ *                    (taken with probability one, weight 1 in Eq. 2);
+ *   slots k_h..      k_r independent uniform draws from [0,L) minus H_i, H_i the
+ *                    distinct in-range ids of the row (u_i of them; u_i = k_h for
+ *                    a mined shortlist), logq = log(k_r / (L - u_i)): the log of
+ *                    the expected number of copies of a label, so exp(-logq) is
+ *                    the 1/(p k_r) factor of Eq. 2.
+ * shortlist == NULL selects the warm-up phase (Alg. 1, t < tau_s): all k_h+k_r
+ * slots are uniform draws from [0,L) and logq = log((k_h+k_r)/L).
+ * Draw j of query i is element r = floor(u*M / 2^64) of the complement, M its
+ * size, u = fmix(fmix(seed ^ K1*(i+1)) + K2*(j+1)) with fmix the splitmix64
+ * finaliser, K1 = 0x9E3779B97F4A7C15, K2 = 0xD1B54A32D192ED03 (64-bit wrapping).
+ * Integer arithmetic only: the ids depend on (seed, i, j, shortlist row) and on
+ * nothing else.  Requires 0 <= k_h <= XC_MAX_K_SAMPLE, k_h < L, k_h + k_r >= 1.
+ * ------------------------------------------------------------------------- */
+int xc_sample_negatives(const int32_t* shortlist /* [B*k_h] or NULL */, int64_t B, int k_h,
+                        int k_r, int64_t L, uint64_t seed,
+                        int32_t* neg /* [B*(k_h+k_r)] out */,
+                        float* logq /* [B*(k_h+k_r)] out */, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * One training step of the classifier layer (Alg. 1: scores on positives and
+ * sampled negatives, loss of Eq. 2, SGD on W; loss averaged over the batch).
+ * Per query i with score s = <z_i, w_l> on the pre-update W:
+ *   BCE      loss_i = sum_{l in pos_i} log(1+e^-s)
+ *                   + sum_{j} m_ij e^{-logq_ij} (s + log(1+e^-s)),
+ *            m_ij = 0 if neg_ij is padding or one of pos_i (the (1-y_l) factor);
+ *   SOFTMAX  logits s - logq over pos_i and the unmasked negatives,
+ *            loss_i = mean over pos_i of -log softmax (a query without a
+ *            positive is skipped).
+ *   loss[0] = (1/B) sum_i loss_i;  dZ = d loss / d Z (fp32, [B*d]);
+ *   w_l <- w_l - lr * d loss / d w_l for every label in an unmasked pair;
+ *   a label in several pairs gets the summed gradient, added in order of
+ *   increasing (i, slot), and is written once (rounded to nearest even for bf16).
+ *   touched[0..n_touched[0]) = those labels, ascending; no other row changes.
+ *   W_rows_out, if not NULL, receives the updated rows in that order.
+ * Z and dZ must not alias.  Requires B >= 1, k_p >= 0, n_neg >= 0,
+ * 1 <= k_p + n_neg <= XC_MAX_CANDIDATES, B*(k_p+n_neg) < 2^31,
+ * d*sizeof(element) a multiple of 16 and <= XC_MAX_ROW_BYTES.
+ * The workspace size does not depend on L.
+ * ------------------------------------------------------------------------- */
+int xc_step_workspace(int64_t B, int d, int k_p, int n_neg, xc_dtype t, size_t* bytes);
+int xc_step(const void* Z /* [B*d] */, void* W /* [L*d], updated in place */, int64_t B,
+            int64_t L, int d, const int32_t* pos /* [B*k_p] */, int k_p,
+            const int32_t* neg /* [B*n_neg] */, const float* logq /* [B*n_neg] */, int n_neg,
+            float lr, xc_loss kind, xc_dtype t, float* loss /* [1] out */,
+            float* dZ /* [B*d] out */, int32_t* touched /* [B*(k_p+n_neg)] out */,
+            int32_t* n_touched /* [1] out */, void* W_rows_out /* [B*(k_p+n_neg)*d] or NULL */,
+            void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASTRA_XC_H */

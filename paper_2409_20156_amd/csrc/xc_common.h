@@ -1,0 +1,96 @@
+// Shared host/device helpers of the gfx950 library: status handling, element
+// conversion, order-preserving score keys and wave-level primitives.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "astra_xc.h"
+
+namespace xc {
+
+constexpr int kWave = 64;
+
+// ---- status ---------------------------------------------------------------
+void set_last_hip_error(hipError_t e);
+
+#define XC_HIP_CHECK(expr)                         \
+    do {                                           \
+        hipError_t e__ = (expr);                   \
+        if (e__ != hipSuccess) {                   \
+            ::xc::set_last_hip_error(e__);         \
+            return XC_EHIP;                        \
+        }                                          \
+    } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- element types ----------------------------------------------------------
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// round-to-nearest-even float -> bf16 bits (NaN kept quiet)
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// unpack 8 bf16 (one 16-byte chunk) into 8 floats
+__device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+
+// ---- order-preserving keys --------------------------------------------------
+// A candidate (score, id) is packed into one 64-bit key whose ascending order is
+// "larger score first, then smaller id": high word = complement of the monotone
+// integer image of the float, low word = id.
+__device__ __forceinline__ uint32_t float_to_ordered(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ordered_to_float(uint32_t o) {
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
+}
+__device__ __forceinline__ uint64_t make_key(float score, int32_t id) {
+    return (static_cast<uint64_t>(~float_to_ordered(score)) << 32) | static_cast<uint32_t>(id);
+}
+__device__ __forceinline__ float key_score(uint64_t k) {
+    return ordered_to_float(~static_cast<uint32_t>(k >> 32));
+}
+__device__ __forceinline__ int32_t key_id(uint64_t k) { return static_cast<int32_t>(k & 0xffffffffu); }
+constexpr uint64_t kKeySentinel = ~0ull;   // score -NaN pattern never produced, id -1
+
+// ---- wave helpers -----------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+__device__ __forceinline__ int wave_incl_scan(int v) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        int t = __shfl_up(v, off, kWave);
+        if (lane >= off) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        uint64_t t = __shfl_xor(v, off, kWave);
+        v = t > v ? t : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint64_t lanemask_lt() {
+    return (1ull << lane_id()) - 1ull;
+}
+
+}  // namespace xc

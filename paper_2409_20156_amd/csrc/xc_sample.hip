@@ -1,0 +1,127 @@
+// Negative sampling: the stale hard negatives of each query plus uniform draws
+// from the remaining labels, with the log-proposal of every slot (Alg. 1,
+// hard+random step; Sec. 3.1 Idea 2; p = 1/(L-k_h) under Eq. 2; warm-up phase
+// of Alg. 1 when no shortlist is given).  Integer arithmetic only, so the ids
+// are a function of (seed, query, draw, shortlist row) and of no launch shape.
+#include "xc_common.h"
+
+namespace xc {
+
+constexpr int kSampleThreads = 256;
+constexpr uint64_t kQueryMul = 0x9E3779B97F4A7C15ull;
+constexpr uint64_t kDrawMul = 0xD1B54A32D192ED03ull;
+
+__device__ __forceinline__ uint64_t fmix64(uint64_t x) {
+    x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27; x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+
+// One workgroup per query.  The shortlist row is sorted in LDS (bitonic, padded
+// to a power of two with INT_MAX), reduced to its distinct in-range ids h_0 <
+// h_1 < ..., and stored as a_m = h_m - m, which is non-decreasing.  Draw r in
+// [0, M) then maps to the r-th label of the complement: r + #{m : a_m <= r}.
+__global__ __launch_bounds__(kSampleThreads)
+void sample_kernel(const int32_t* __restrict__ shortlist, int k_h, int k_r, int64_t L,
+                   uint64_t seed, int n2, int32_t* __restrict__ neg, float* __restrict__ logq) {
+    __shared__ int32_t hs[XC_MAX_K_SAMPLE];
+    __shared__ int32_t adj[XC_MAX_K_SAMPLE];
+    __shared__ int n_unique;
+    const int64_t i = blockIdx.x;
+    const int n = k_h + k_r;
+    int32_t* out = neg + i * n;
+    float* lq = logq + i * n;
+    int u = 0, n_draw = n, first = 0;
+
+    if (shortlist != nullptr) {
+        const int32_t* row = shortlist + i * k_h;
+        for (int m = threadIdx.x; m < n2; m += blockDim.x) {
+            int32_t v = 0x7fffffff;
+            if (m < k_h) {
+                const int32_t id = row[m];
+                out[m] = id;
+                lq[m] = 0.0f;
+                if (id >= 0 && id < L) v = id;
+            }
+            hs[m] = v;
+        }
+        if (threadIdx.x == 0) n_unique = 0;
+        __syncthreads();
+        for (int size = 2; size <= n2; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                for (int t = threadIdx.x; t < n2 / 2; t += blockDim.x) {
+                    const int lo = 2 * t - (t & (stride - 1));
+                    const int hi = lo + stride;
+                    const bool up = (lo & size) == 0;
+                    const int32_t a = hs[lo], b = hs[hi];
+                    if ((a > b) == up) { hs[lo] = b; hs[hi] = a; }
+                }
+                __syncthreads();
+            }
+        }
+        // distinct valid ids, in order: position = number of distinct ids before m
+        for (int m0 = 0; m0 < n2; m0 += blockDim.x) {
+            const int m = m0 + threadIdx.x;
+            bool head = false;
+            int32_t v = 0;
+            if (m < n2) {
+                v = hs[m];
+                head = v != 0x7fffffff && (m == 0 || hs[m - 1] != v);
+            }
+            // block-wide exclusive count of heads below m within this chunk
+            const uint64_t bal = __ballot(head);
+            __shared__ int wave_cnt[kSampleThreads / kWave];
+            const int w = threadIdx.x >> 6;
+            if (lane_id() == 0) wave_cnt[w] = __popcll(bal);
+            __syncthreads();
+            int before = n_unique;
+            for (int ww = 0; ww < w; ++ww) before += wave_cnt[ww];
+            const int p = before + __popcll(bal & lanemask_lt());
+            int chunk_total = 0;
+            for (int ww = 0; ww < kSampleThreads / kWave; ++ww) chunk_total += wave_cnt[ww];
+            __syncthreads();
+            if (head) adj[p] = v - p;
+            if (threadIdx.x == 0) n_unique += chunk_total;
+            __syncthreads();
+        }
+        u = n_unique;
+        n_draw = k_r;
+        first = k_h;
+    }
+
+    const uint64_t M = static_cast<uint64_t>(L) - static_cast<uint64_t>(u);
+    const uint64_t qstate = fmix64(seed ^ (kQueryMul * static_cast<uint64_t>(i + 1)));
+    // log of the expected number of copies of a label among the draws
+    const float lq_rand = static_cast<float>(log(static_cast<double>(n_draw) / static_cast<double>(M)));
+    for (int j = threadIdx.x; j < n_draw; j += blockDim.x) {
+        const uint64_t w = fmix64(qstate + kDrawMul * static_cast<uint64_t>(j + 1));
+        const uint64_t r = __umul64hi(w, M);
+        // count of a_m <= r by binary search over the non-decreasing a
+        int lo = 0, hi = u;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (static_cast<uint64_t>(adj[mid]) <= r) lo = mid + 1; else hi = mid;
+        }
+        out[first + j] = static_cast<int32_t>(r + static_cast<uint64_t>(lo));
+        lq[first + j] = lq_rand;
+    }
+}
+
+}  // namespace xc
+
+extern "C" int xc_sample_negatives(const int32_t* shortlist, int64_t B, int k_h, int k_r, int64_t L,
+                                   uint64_t seed, int32_t* neg, float* logq, void* stream) {
+    using namespace xc;
+    if (B < 1 || k_h < 0 || k_r < 0 || k_h + k_r < 1 || k_h > XC_MAX_K_SAMPLE) return XC_ESHAPE;
+    if (L < 1 || L > 0x7fffffffLL || k_h >= L) return XC_ESHAPE;
+    if (B > 0x7fffffffLL) return XC_ESHAPE;
+    if (!neg || !logq) return XC_EINVAL;
+    int n2 = 2;
+    while (n2 < k_h) n2 <<= 1;
+    if (k_h == 0) shortlist = nullptr;      // nothing to exclude: same as the warm-up draw
+    sample_kernel<<<dim3(static_cast<unsigned>(B)), kSampleThreads, 0, static_cast<hipStream_t>(stream)>>>(
+        shortlist, k_h, k_r, L, seed, n2, neg, logq);
+    XC_HIP_CHECK(hipGetLastError());
+    return XC_OK;
+}

@@ -1,0 +1,67 @@
+"""The C-ABI library loads and exports every entry point the header declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "astra_xc.h")
+LIB = os.path.join(ROOT, "paper_2409_20156_amd", "libastra_xc.so")
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(xc_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2409_20156_amd.build import build
+        build()
+    return ctypes.CDLL(LIB)
+
+
+def test_header_declares_the_three_calls():
+    names = _declared()
+    for n in ("xc_mine_negatives", "xc_sample_negatives", "xc_step", "xc_mine_workspace",
+              "xc_step_workspace", "xc_strerror", "xc_last_hip_error", "xc_version"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for n in _declared():
+        assert hasattr(lib, n), n
+
+
+def test_binding_covers_every_declared_symbol():
+    from paper_2409_20156_amd import binding
+    assert binding.exported_symbols() == _declared()
+
+
+def test_host_side_argument_checks(lib):
+    """Shape and pointer errors are reported before anything touches a device."""
+    from paper_2409_20156_amd import binding
+    b = binding.load_library()
+    n = ctypes.c_size_t(0)
+    assert b.xc_mine_workspace(128, 1000, 64, 8, 1, ctypes.byref(n)) == 0 and n.value > 0
+    assert b.xc_mine_workspace(128, 1000, 64, 129, 1, ctypes.byref(n)) == -2      # k_h too large
+    assert b.xc_mine_workspace(128, 4, 64, 8, 1, ctypes.byref(n)) == -2           # k_h > L
+    assert b.xc_mine_workspace(128, 1000, 60, 8, 1, ctypes.byref(n)) == -2        # row not 16-byte multiple
+    assert b.xc_mine_workspace(128, 1000, 64, 8, 7, ctypes.byref(n)) == -1        # bad dtype
+    assert b.xc_mine_workspace(128, 1000, 64, 8, 1, None) == -1
+    assert b.xc_step_workspace(32, 64, 1, 24, 0, ctypes.byref(n)) == 0 and n.value > 0
+    big = n.value
+    assert b.xc_step_workspace(32, 64, 0, 0, 0, ctypes.byref(n)) == -2            # no candidates
+    assert b.xc_step_workspace(32, 4096, 1, 24, 1, ctypes.byref(n)) == -2         # row too long
+    assert b.xc_step_workspace(32, 64, 1, 20000, 0, ctypes.byref(n)) == -2
+    # null pointers / k_h >= L are rejected without a launch
+    assert b.xc_sample_negatives(None, 4, 8, 16, 8, 1, None, None, None) == -2
+    assert b.xc_sample_negatives(None, 4, 8, 16, 100, 1, None, None, None) == -1
+    assert b.xc_mine_negatives(None, None, 1, 100, 64, 8, 1, None, None, None, 0, None) == -1
+    assert b.xc_step(None, None, 32, 4096, 64, None, 1, None, None, 24, 0.1, 0, 0, None, None, None,
+                     None, None, None, big, None) == -1
+    assert b.xc_strerror(-2).decode().startswith("unsupported")
+    assert b.xc_version() >= 1

@@ -1,0 +1,95 @@
+"""GPU parity of xc_mine_negatives against the oracle's exact top-k."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import astra_oracle as orc
+from paper_2409_20156_amd import synth
+from tests.parity import check_topk, f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(Z, W, k):
+    import paper_2409_20156_amd as xc
+    ids, sc = xc.mine_negatives(Z, W, k, want_scores=True)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), sc.cpu().numpy()
+
+
+def _case(seed, Zq, L, d, dtype, k):
+    dev = "cuda:0"
+    W = synth.make_matrix(seed, synth.TAG_W, L, d, dtype, dev)
+    Z = synth.make_matrix(seed, synth.TAG_Z, Zq, d, dtype, dev)
+    ids, sc = _run(Z, W, k)
+    Z64, W64 = f64(Z), f64(W)
+    ids_o, sc_o = orc.mine_negatives(Z64, W64, k)
+    n_tied = check_topk(ids, sc, ids_o, sc_o, Z64, W64)
+    for i in range(Zq):                      # invariants that hold at any size
+        assert len(set(ids[i].tolist())) == k
+        assert (np.diff(sc[i]) <= 0).all()
+    return n_tied
+
+
+@pytest.mark.parametrize("Zq,L,d,dtype,k", [
+    (32, 4096, 64, torch.float32, 8),          # the Tiny configuration
+    (200, 5000, 72, torch.bfloat16, 50),       # ragged query tile, ragged label tile, K tail
+    (130, 1000, 40, torch.float32, 100),       # fp32 K tail (160-byte rows)
+    (1, 300, 64, torch.bfloat16, 1),
+    (3, 64, 64, torch.bfloat16, 64),           # k = L, single partial tile
+    (257, 3000, 768, torch.bfloat16, 128),     # maximum k, d of the large configurations
+    (5, 129, 8, torch.bfloat16, 7),            # minimum row (16 bytes)
+])
+def test_mine_matches_oracle(Zq, L, d, dtype, k):
+    print("case", Zq, L, d, dtype, k, flush=True)
+    _case(11, Zq, L, d, dtype, k)
+
+
+def test_mine_long_slices_exercise_list_reduction():
+    # 512 queries x 131072 labels: 4096 labels per slice, so candidate lists fill and are reduced
+    print("case long slices", flush=True)
+    _case(5, 512, 131072, 64, torch.bfloat16, 64)
+
+
+def test_mine_increasing_scores_worst_case_for_the_threshold():
+    # score(i, l) grows with l: every label beats the running threshold
+    dev = "cuda:0"
+    L, d, Zq, k = 40000, 16, 140, 33
+    base = torch.ones(d, dtype=torch.float32)
+    W = (torch.arange(L, dtype=torch.float32)[:, None] / 65536.0 * base[None, :]).to(torch.bfloat16).to(dev)
+    Z = torch.ones((Zq, d), dtype=torch.bfloat16, device=dev)
+    Z[1::2] *= -1.0                                  # odd queries prefer small ids
+    ids, sc = _run(Z, W, k)
+    Z64, W64 = f64(Z), f64(W)
+    ids_o, sc_o = orc.mine_negatives(Z64, W64, k)
+    check_topk(ids, sc, ids_o, sc_o, Z64, W64)
+    assert (ids == ids_o).all()                      # bf16 products of these values are exact: no tolerance needed
+
+
+def test_mine_all_scores_equal_orders_by_id():
+    dev = "cuda:0"
+    W = torch.zeros((3000, 64), dtype=torch.bfloat16, device=dev)
+    Z = synth.make_matrix(1, synth.TAG_Z, 70, 64, torch.bfloat16, dev)
+    ids, sc = _run(Z, W, 20)
+    assert (ids == np.arange(20)[None, :]).all()
+    assert (sc == 0).all()
+
+
+def test_mine_planted_rows_come_first():
+    dev = "cuda:0"
+    L, d, Zq, k = 20000, 128, 64, 10
+    W = synth.make_matrix(2, synth.TAG_W, L, d, torch.bfloat16, dev)
+    Z = synth.make_matrix(2, synth.TAG_Z, Zq, d, torch.bfloat16, dev)
+    plant = (torch.arange(Zq) * 311 + 7) % L
+    W[plant.to(dev)] = (Z.float() * 8.0).to(torch.bfloat16)       # <z, 8 z> dwarfs every random score
+    ids, _ = _run(Z, W, k)
+    assert (ids[:, 0] == plant.numpy()).all()
+
+
+def test_mine_is_reproducible_run_to_run():
+    dev = "cuda:0"
+    W = synth.make_matrix(3, synth.TAG_W, 30000, 64, torch.bfloat16, dev)
+    Z = synth.make_matrix(3, synth.TAG_Z, 300, 64, torch.bfloat16, dev)
+    a = _run(Z, W, 64)
+    b = _run(Z, W, 64)
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all()

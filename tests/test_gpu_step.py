@@ -1,0 +1,118 @@
+"""GPU parity of xc_step against the oracle: loss, dZ, touched ids, updated rows."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import astra_oracle as orc
+from paper_2409_20156_amd import synth
+from tests.parity import TOL, check_bf16_rows, check_rows_close, dtype_name, f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(seed, B, L, d, dtype, k_p, k_h, k_r, zipf=1.0, law="uniform:1:3"):
+    dev = "cuda:0"
+    W = synth.make_matrix(seed, synth.TAG_W, L, d, dtype, dev)
+    Z = synth.make_matrix(seed, synth.TAG_Z, B, d, dtype, dev)
+    pos = synth.zipf_positives(seed, B, L, zipf, law if k_p > 1 else "one", k_p)
+    Z = synth.add_positive_signal(Z, W, pos)
+    Z64, W64 = f64(Z), f64(W)
+    sl, _ = orc.mine_negatives(Z64, W64, k_h) if k_h else (np.zeros((B, 0), np.int32), None)
+    neg, logq = orc.sample_negatives(sl, B, k_h, k_r, L, seed=seed + 17)
+    return Z, W, pos, neg, logq, Z64, W64
+
+
+def _run_and_check(Z, W, pos, neg, logq, Z64, W64, lr, kind):
+    import paper_2409_20156_amd as xc
+    name = dtype_name(Z)
+    tol = TOL[name]
+    dev = Z.device
+    Wg = W.clone()
+    out = xc.xc_step(Z, Wg, torch.tensor(pos, device=dev), torch.tensor(neg, device=dev),
+                     torch.tensor(logq, device=dev), lr, kind=kind, want_rows=True)
+    torch.cuda.synchronize()
+    ref = orc.xc_step(Z64, W64, pos, neg, logq, lr, kind=kind, storage=name)
+    loss = float(out["loss"].item())
+    assert abs(loss - ref["loss"]) <= tol * abs(ref["loss"]), (loss, ref["loss"])
+    check_rows_close(out["dZ"].cpu().numpy(), ref["dZ"], tol, "dZ")
+    nt = int(out["n_touched"].item())
+    touched = out["touched"][:nt].cpu().numpy()
+    assert nt == len(ref["touched"]) and (touched == ref["touched"]).all()
+    rows = f64(out["W_rows"][:nt])
+    new = f64(Wg)
+    assert (new[touched] == rows).all()                          # W_rows_out is a copy of the stored rows
+    if name == "f32":
+        # the update itself must match to the float tolerance
+        # ... up to the float32 rounding of the stored row itself (one ulp of w per side)
+        dg, dw = rows - W64[touched], ref["W_rows"] - W64[touched]
+        slack = 2.0 ** -23 * np.abs(W64[touched]).max(axis=1, keepdims=True)
+        scale = np.abs(dw).max(axis=1, keepdims=True)
+        assert (np.abs(dg - dw) <= 5 * tol * scale + slack).all(), "delta W"
+        check_rows_close(rows, ref["W_rows"], tol, "W rows")
+    else:
+        check_bf16_rows(rows, ref["W_rows"], W64[touched], "W rows")
+    mask = np.ones(W64.shape[0], bool)
+    mask[touched] = False
+    assert (new[mask] == W64[mask]).all()                        # untouched rows are bit-identical
+    return out, ref
+
+
+@pytest.mark.parametrize("kind", [orc.LOSS_BCE, orc.LOSS_SOFTMAX])
+@pytest.mark.parametrize("B,L,d,dtype,k_p,k_h,k_r", [
+    (32, 4096, 64, torch.float32, 1, 8, 16),          # Tiny
+    (37, 500, 72, torch.bfloat16, 3, 5, 40),          # heavy duplicates, ragged everything
+    (20, 3000, 20, torch.float32, 2, 4, 30),          # 80-byte fp32 rows
+    (48, 20000, 768, torch.bfloat16, 4, 64, 256),     # config-2 row shape
+    (16, 9000, 256, torch.bfloat16, 3, 50, 300),      # config-5 row shape
+    (9, 2000, 2048, torch.bfloat16, 2, 8, 24),        # longest supported row
+])
+def test_step_matches_oracle(B, L, d, dtype, k_p, k_h, k_r, kind):
+    print("case", B, L, d, dtype, k_p, k_h, k_r, kind, flush=True)
+    Z, W, pos, neg, logq, Z64, W64 = _inputs(3, B, L, d, dtype, k_p, k_h, k_r)
+    lr = 0.05 if dtype == torch.bfloat16 else 0.3
+    _run_and_check(Z, W, pos, neg, logq, Z64, W64, lr, kind)
+
+
+def test_step_masks_positives_and_padding_and_out_of_range_ids():
+    B, L, d = 4, 300, 64
+    Z, W, pos, neg, logq, Z64, W64 = _inputs(5, B, L, d, torch.float32, 3, 4, 12)
+    neg[0, 2] = pos[0, 0]           # a positive among the hard negatives
+    neg[1, 7] = pos[1, 0]           # ... and among the random ones
+    neg[2, 3] = -1
+    neg[3, 5] = L + 5               # out of range: ignored, not dereferenced
+    pos[3, 2] = L
+    for kind in (orc.LOSS_BCE, orc.LOSS_SOFTMAX):
+        _run_and_check(Z, W, pos, neg, logq, Z64, W64, 0.2, kind)
+
+
+def test_step_shared_positive_is_summed_once_per_pair():
+    B, L, d = 64, 100, 64
+    Z, W, pos, neg, logq, Z64, W64 = _inputs(6, B, L, d, torch.float32, 1, 2, 6)
+    pos[:, 0] = 42
+    out, ref = _run_and_check(Z, W, pos, neg, logq, Z64, W64, 0.1, orc.LOSS_BCE)
+    assert 42 in ref["touched"]
+
+
+def test_step_without_negatives_or_without_positives():
+    B, L, d = 8, 200, 64
+    Z, W, pos, neg, logq, Z64, W64 = _inputs(7, B, L, d, torch.float32, 2, 3, 9)
+    empty_i = np.zeros((B, 0), np.int32)
+    empty_f = np.zeros((B, 0), np.float32)
+    _run_and_check(Z, W, pos, empty_i, empty_f, Z64, W64, 0.1, orc.LOSS_BCE)
+    _run_and_check(Z, W, empty_i, neg, logq, Z64, W64, 0.1, orc.LOSS_BCE)
+    _run_and_check(Z, W, np.full((B, 2), -1, np.int32), neg, logq, Z64, W64, 0.1, orc.LOSS_SOFTMAX)
+
+
+def test_step_is_bitwise_reproducible():
+    import paper_2409_20156_amd as xc
+    Z, W, pos, neg, logq, _, _ = _inputs(8, 40, 1000, 768, torch.bfloat16, 4, 16, 100)
+    dev = Z.device
+    res = []
+    for _ in range(2):
+        Wg = W.clone()
+        out = xc.xc_step(Z, Wg, torch.tensor(pos, device=dev), torch.tensor(neg, device=dev),
+                         torch.tensor(logq, device=dev), 0.05)
+        torch.cuda.synchronize()
+        res.append((out["loss"].cpu(), out["dZ"].cpu(), Wg.cpu()))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+    assert torch.equal(res[0][2].view(torch.int16), res[1][2].view(torch.int16))
