@@ -121,6 +121,21 @@ int xc_step(const void* Z /* [B*d] */, void* W /* [L*d], updated in place */, in
             int32_t* n_touched /* [1] out */, void* W_rows_out /* [B*(k_p+n_neg)*d] or NULL */,
             void* ws, size_t ws_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Measurement aid (no passage of the paper: used by the benchmark to time each
+ * kernel with HIP events on the stream it is launched on).  While enabled, every
+ * kernel launch of the three calls above is bracketed by a pair of events.
+ * xc_profile_collect() waits for the recorded events (host-side wait), adds the
+ * elapsed times to per-kernel totals and returns the number of kernel names;
+ * xc_profile_get(i, ...) reads total milliseconds and launch count of name i;
+ * xc_profile_reset() clears the totals.  Off by default; when off the calls
+ * above record no events.  Not thread-safe against concurrent launches.
+ * ------------------------------------------------------------------------- */
+int xc_profile_enable(int on);
+int xc_profile_collect(void);
+int xc_profile_get(int i, const char** name, double* total_ms, int64_t* launches);
+int xc_profile_reset(void);
+
 #ifdef __cplusplus
 }
 #endif

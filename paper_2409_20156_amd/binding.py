@@ -29,6 +29,11 @@ _SIGNATURES = {
                                  ctypes.c_size_t, _ptr]),
     "xc_sample_negatives": (_i32, [_ptr, _i64, _i32, _i32, _i64, _u64, _ptr, _ptr, _ptr]),
     "xc_step_workspace": (_i32, [_i64, _i32, _i32, _i32, _i32, _szp]),
+    "xc_profile_enable": (_i32, [_i32]),
+    "xc_profile_collect": (_i32, []),
+    "xc_profile_get": (_i32, [_i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
+                              ctypes.POINTER(ctypes.c_int64)]),
+    "xc_profile_reset": (_i32, []),
     "xc_step": (_i32, [_ptr, _ptr, _i64, _i64, _i32, _ptr, _i32, _ptr, _ptr, _i32, _f32, _i32, _i32,
                        _ptr, _ptr, _ptr, _ptr, _ptr, _ptr, ctypes.c_size_t, _ptr]),
 }
@@ -190,3 +195,23 @@ def xc_step(Z: torch.Tensor, W: torch.Tensor, pos: torch.Tensor, neg: torch.Tens
                        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
            "xc_step")
     return {"loss": loss, "dZ": dZ, "touched": touched, "n_touched": n_touched, "W_rows": rows}
+
+
+def profile_enable(on: bool) -> None:
+    _check(load_library().xc_profile_enable(1 if on else 0), "xc_profile_enable")
+
+
+def profile_reset() -> None:
+    _check(load_library().xc_profile_reset(), "xc_profile_reset")
+
+
+def profile_collect() -> dict:
+    """Per-kernel {name: (total_ms, launches)} of the launches made while profiling was on."""
+    lib = load_library()
+    n = lib.xc_profile_collect()
+    out = {}
+    for i in range(n):
+        name, ms, cnt = ctypes.c_char_p(), ctypes.c_double(), ctypes.c_int64()
+        _check(lib.xc_profile_get(i, ctypes.byref(name), ctypes.byref(ms), ctypes.byref(cnt)), "xc_profile_get")
+        out[name.value.decode()] = (ms.value, cnt.value)
+    return out

@@ -23,6 +23,24 @@ void set_last_hip_error(hipError_t e);
         }                                          \
     } while (0)
 
+// ---- optional per-kernel event timing ----------------------------------------
+enum KernelId {
+    K_MINE_TILE = 0, K_MINE_MERGE, K_SAMPLE, K_GATHER, K_LOSS_REDUCE, K_RADIX_COUNT, K_RADIX_SCAN,
+    K_RADIX_SCATTER, K_HEADS_COUNT, K_HEADS_WRITE, K_UPDATE, K_NUM_KERNELS
+};
+bool profile_on();
+void profile_mark(int kernel_id, hipStream_t st, bool begin);
+
+// Launch statement `stmt` for kernel `id` on stream `st`, bracketed by events when
+// profiling is enabled.
+#define XC_LAUNCH(id, st, stmt)                                   \
+    do {                                                          \
+        const bool prof__ = ::xc::profile_on();                   \
+        if (prof__) ::xc::profile_mark((id), (st), true);         \
+        stmt;                                                     \
+        if (prof__) ::xc::profile_mark((id), (st), false);        \
+    } while (0)
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

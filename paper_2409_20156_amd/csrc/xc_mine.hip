@@ -374,17 +374,17 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
     const dim3 grid(static_cast<unsigned>(p.nQT * p.S));
     uint64_t* cand = static_cast<uint64_t*>(ws);
     if (t == XC_BF16) {
-        mine_tile_kernel<bf16_t><<<grid, kMineThreads, 0, st>>>(
+        XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t><<<grid, kMineThreads, 0, st>>>(
             static_cast<const bf16_t*>(Z), static_cast<const bf16_t*>(W), Zq, L, d, k_h, p.kcap, p.S,
-            p.tiles_per_slice, cand);
+            p.tiles_per_slice, cand)));
     } else {
-        mine_tile_kernel<float><<<grid, kMineThreads, 0, st>>>(
+        XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<float><<<grid, kMineThreads, 0, st>>>(
             static_cast<const float*>(Z), static_cast<const float*>(W), Zq, L, d, k_h, p.kcap, p.S,
-            p.tiles_per_slice, cand);
+            p.tiles_per_slice, cand)));
     }
     XC_HIP_CHECK(hipGetLastError());
-    mine_merge_kernel<<<dim3(static_cast<unsigned>(Zq)), 256, 0, st>>>(cand, p.S, p.kcap, k_h, p.n2,
-                                                                       shortlist, scores);
+    XC_LAUNCH(K_MINE_MERGE, st, (mine_merge_kernel<<<dim3(static_cast<unsigned>(Zq)), 256, 0, st>>>(
+        cand, p.S, p.kcap, k_h, p.n2, shortlist, scores)));
     XC_HIP_CHECK(hipGetLastError());
     return XC_OK;
 }

@@ -120,8 +120,9 @@ extern "C" int xc_sample_negatives(const int32_t* shortlist, int64_t B, int k_h,
     int n2 = 2;
     while (n2 < k_h) n2 <<= 1;
     if (k_h == 0) shortlist = nullptr;      // nothing to exclude: same as the warm-up draw
-    sample_kernel<<<dim3(static_cast<unsigned>(B)), kSampleThreads, 0, static_cast<hipStream_t>(stream)>>>(
-        shortlist, k_h, k_r, L, seed, n2, neg, logq);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_SAMPLE, st, (sample_kernel<<<dim3(static_cast<unsigned>(B)), kSampleThreads, 0, st>>>(
+        shortlist, k_h, k_r, L, seed, n2, neg, logq)));
     XC_HIP_CHECK(hipGetLastError());
     return XC_OK;
 }

@@ -585,9 +585,9 @@ static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, con
     const float inv_B = 1.0f / static_cast<float>(B);
     const dim3 grid(static_cast<unsigned>(B));
 #define XC_GATHER(CPL)                                                                              \
-    gather_kernel<T, CPL, KIND><<<grid, kStepThreads, 0, st>>>(                                     \
+    XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND><<<grid, kStepThreads, 0, st>>>(            \
         static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg, pl.G, \
-        inv_B, keys, vals, gco, loss_q, dZ)
+        inv_B, keys, vals, gco, loss_q, dZ)))
     switch (pl.cpl) {
         case 1: XC_GATHER(1); break;
         case 2: XC_GATHER(2); break;
@@ -604,9 +604,9 @@ static void launch_update(const StepPlan& pl, hipStream_t st, const void* Z, voi
     const int NG = kStepThreads / pl.G;
     const dim3 grid(static_cast<unsigned>((pl.P + NG - 1) / NG));
 #define XC_UPDATE(CPL)                                                                            \
-    update_kernel<T, CPL><<<grid, kStepThreads, 0, st>>>(static_cast<const T*>(Z), static_cast<T*>(W), d, \
-                                                         pl.n, pl.G, vals, gco, touched, seg_start,     \
-                                                         n_touched, lr, static_cast<T*>(rows_out))
+    XC_LAUNCH(K_UPDATE, st, (update_kernel<T, CPL><<<grid, kStepThreads, 0, st>>>(                \
+        static_cast<const T*>(Z), static_cast<T*>(W), d, pl.n, pl.G, vals, gco, touched, seg_start, \
+        n_touched, lr, static_cast<T*>(rows_out))))
     switch (pl.cpl) {
         case 1: XC_UPDATE(1); break;
         case 2: XC_UPDATE(2); break;
@@ -673,23 +673,23 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
             launch_gather<float, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dZ);
     }
     XC_HIP_CHECK(hipGetLastError());
-    loss_reduce_kernel<<<1, 256, 0, st>>>(loss_q, B, 1.0f / static_cast<float>(B), loss);
+    XC_LAUNCH(K_LOSS_REDUCE, st, (loss_reduce_kernel<<<1, 256, 0, st>>>(loss_q, B, 1.0f / static_cast<float>(B), loss)));
     XC_HIP_CHECK(hipGetLastError());
 
     // S5: sort pairs by label
     uint32_t *kin = keys0, *kout = keys1, *vin = vals0, *vout = vals1;
     for (int pass = 0; pass < pl.passes; ++pass) {
         const int shift = pass * kRadixBits;
-        radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.nb, counts);
-        scan_kernel<<<1, 1024, 0, st>>>(counts, kRadix * pl.nb);
-        radix_scatter_kernel<<<pl.nb, kSortTile, 0, st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.nb, counts);
+        XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.nb, counts)));
+        XC_LAUNCH(K_RADIX_SCAN, st, (scan_kernel<<<1, 1024, 0, st>>>(counts, kRadix * pl.nb)));
+        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, 0, st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.nb, counts)));
         XC_HIP_CHECK(hipGetLastError());
         uint32_t* tk = kin; kin = kout; kout = tk;
         uint32_t* tv = vin; vin = vout; vout = tv;
     }
-    heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt);
-    heads_write_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
-                                              valid_cnt, touched, seg_start, n_touched);
+    XC_LAUNCH(K_HEADS_COUNT, st, (heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt)));
+    XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
+                                                                            valid_cnt, touched, seg_start, n_touched)));
     XC_HIP_CHECK(hipGetLastError());
     if (t == XC_BF16) launch_update<bf16_t>(pl, st, Z, W, d, vin, gco, touched, seg_start, n_touched, lr, W_rows_out);
     else launch_update<float>(pl, st, Z, W, d, vin, gco, touched, seg_start, n_touched, lr, W_rows_out);
