@@ -222,7 +222,7 @@ def main():
         "kernels_us": {n: round(k["avg_us"], 2) for n, k in kernels.items()},
     }
     if "mine_tile" in kernels:
-        result["mine_pairs_per_s"] = pool * wl.L / ((kernels["mine_tile"]["avg_us"] + kernels.get("mine_merge", {"avg_us": 0})["avg_us"]) * 1e-6)
+        result["mine_pairs_per_s"] = pool * wl.L / ((kernels["mine_tile"]["avg_us"] + kernels.get("mine_select", {"avg_us": 0})["avg_us"]) * 1e-6)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, pool)
     else:

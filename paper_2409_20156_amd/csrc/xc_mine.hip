@@ -2,39 +2,53 @@
 // classifier rows (Alg. 1, "ANNS refresh" step, with exact search in place of
 // the index; score of Sec. 2.1).
 //
-// Kernel 1 (mine_tile_kernel) is a tiled MFMA product W_tile x Z_tile^T whose
-// accumulators never leave registers as a matrix: labels run along the MFMA M
-// dimension and queries along N, so one lane owns one query column and compares
-// its 32 partial scores against that query's running threshold tau (the k-th
-// best score seen so far in this label slice).  Survivors are appended as
-// 64-bit (score,id) keys to a small per-query candidate list; when a list is
-// nearly full one wave reduces it to the best k by a radix select and raises
-// tau.  Kernel 2 (mine_merge_kernel) merges the per-slice lists of a query and
-// emits the k best, ordered by (score descending, id ascending).
+// The labels are swept in phases of geometrically growing size (256 labels,
+// then 8x more each time).  Within a phase every query has a FIXED threshold
+// tau: the exact k-th best score over all labels of the earlier phases, so the
+// k best labels overall are never below it and only about 8k scores per query
+// pass it.
+//   mine_tile_kernel    persistent tiled MFMA product W_tile x Z_tile^T (256
+//       labels x 256 queries per workgroup, 8 waves of 128 x 64).  Labels run
+//       along the MFMA M axis and queries along N, so one lane owns one query
+//       column and compares its accumulators with that query's tau; the score
+//       matrix never leaves registers.  Survivors go, as 64-bit (score,id)
+//       keys, to a 512-key list per query and are appended to the query's
+//       global candidate list when the workgroup finishes its label slice.  A
+//       list that could overflow is cut to its best k by one wave (radix
+//       select) and tau rises locally: only adversarial score orders get there.
+//   mine_select_kernel  after each phase, one wave per query cuts the global
+//       candidate list to its best k and publishes the new tau; after the last
+//       phase it sorts the winners by (score descending, id ascending).
 #include "xc_common.h"
 
 namespace xc {
 
-constexpr int kBM = 128;            // labels per tile   (MFMA M)
-constexpr int kBN = 128;            // queries per tile  (MFMA N)
+constexpr int kBM = 256;            // labels per tile   (MFMA M)
+constexpr int kBN = 256;            // queries per tile  (MFMA N)
 constexpr int kStageBytes = 128;    // bytes of a row staged in LDS per K step
-constexpr int kRowStride = kStageBytes + 16;   // padded LDS row pitch
-constexpr int kCandCap = 512;       // keys per (query, slice) candidate list
-constexpr int kMineThreads = 256;   // 4 waves: 2 along labels x 2 along queries
-constexpr int kMergeMax = 4096;     // keys merged per query
+constexpr int kRowStride = kStageBytes + 16;   // padded LDS row pitch (conflict-free 16-byte reads)
+constexpr int kCandCap = 512;       // keys per query candidate list
+constexpr int kMineThreads = 512;   // 8 waves: 2 along labels x 4 along queries
+constexpr int kMineWaves = kMineThreads / kWave;
+constexpr int kMineGrid = 256;      // persistent workgroups, one per compute unit
+constexpr int kXcds = 8;            // workgroup w runs on XCD w % 8
+constexpr int kCusPerXcd = kMineGrid / kXcds;
+constexpr int kPhaseGrowth = 8;     // labels of a phase / labels before it
+constexpr int kSelectRegs = 16;     // keys per lane held in registers by the phase select
+constexpr uint32_t kTauInit = 0x007fffffu;   // ordered image of -inf
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // ---------------------------------------------------------------------------
 // Reduce a candidate list of n > k keys to its k smallest keys (best scores).
-// One wave; n <= kCandCap.  Radix select, most significant byte first, with a
+// One wave; n <= 64*R keys, held in registers.  Radix select, most significant byte first, with a
 // 256-bin histogram in LDS; stops as soon as every key sharing the prefix is
 // needed.  Writes the survivors to buf[0..k), returns the score of the k-th.
 // ---------------------------------------------------------------------------
-__device__ float wave_select_k(uint64_t* __restrict__ buf, int n, int k, int* hist) {
+template <int R>
+__device__ __noinline__ float wave_select_k(uint64_t* __restrict__ buf, int n, int k, int* hist) {
     const int lane = lane_id();
-    constexpr int R = kCandCap / kWave;
     uint64_t key[R];
     bool valid[R];
 #pragma unroll
@@ -124,190 +138,376 @@ template <> struct MineTraits<float> {
     }
 };
 
-// Loads the 16-byte chunks of one K stage of a 128-row tile into registers.
-// Rows beyond `nrows` repeat the last row (their results are discarded later);
-// bytes beyond the row length read as zero.
-__device__ __forceinline__ void load_stage(const unsigned char* __restrict__ base, int64_t row0,
-                                           int64_t nrows, int64_t row_bytes, int kbyte0,
-                                           uint4 (&r)[4]) {
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int c = threadIdx.x + kMineThreads * it;
-        const int row = c >> 3;
-        const int kb = kbyte0 + (c & 7) * 16;
-        int64_t gr = row0 + row;
-        gr = gr < nrows ? gr : nrows - 1;
-        if (kb < row_bytes) {
-            r[it] = *reinterpret_cast<const uint4*>(base + gr * row_bytes + kb);
-        } else {
-            r[it] = make_uint4(0, 0, 0, 0);
-        }
-    }
-}
+struct MineArgs {
+    const unsigned char* Z;
+    const unsigned char* W;
+    int64_t Zq, L, row_bytes;
+    int k, kcap;
+    int nkb;                 // K stages per tile
+    int64_t nQT;             // query tiles
+    int64_t tile_lo, tile_hi;   // label tiles of this phase
+    int64_t tiles_per_slice;
+    int S;                   // label slices of the phase
+    int Qx;                  // > 0: query tiles in flight per XCD (slices bound to XCDs);
+                             // 0: plain order, item = qtile * S + slice
+    int append_max;          // keys one slice may append per query (>= kcap)
+    int glist_cap;           // keys per query in the global candidate lists
+    uint64_t* lists;         // [kMineGrid][kBN][kCandCap] per-workgroup lists
+    uint64_t* glist;         // [nQT*kBN][glist_cap] per-query candidates across slices and phases
+    int32_t* gcnt;           // [nQT*kBN] fill of glist
+    const uint32_t* tau_g;   // [nQT*kBN] ordered image of the phase threshold
+};
 
-__device__ __forceinline__ void store_stage(unsigned char* lds, const uint4 (&r)[4]) {
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int c = threadIdx.x + kMineThreads * it;
-        *reinterpret_cast<uint4*>(lds + (c >> 3) * kRowStride + (c & 7) * 16) = r[it];
-    }
-}
+// One K stage of the W tile and the Z tile is 512 rows x 8 chunks of 16 bytes:
+// 8 chunks per thread (rows r, r+64, r+128, r+192 of W and of Z, r = tid/8, chunk
+// column tid%8).
+struct StageRegs { uint4 w[4], z[4]; };
 
-template <typename T>
-__global__ __launch_bounds__(kMineThreads, 2)
-void mine_tile_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t Zq, int64_t L,
-                      int d, int k, int kcap, int S, int tiles_per_slice,
-                      uint64_t* __restrict__ cand) {
-    __shared__ __align__(16) unsigned char ldsW[kBM * kRowStride];
-    __shared__ __align__(16) unsigned char ldsZ[kBN * kRowStride];
-    __shared__ float tau[kBN];
-    __shared__ int cnt[kBN];
-    __shared__ int hist[kMineThreads / kWave][256];
+template <typename T, bool KTAIL>
+__global__ __launch_bounds__(kMineThreads, 1)
+void mine_tile_kernel(const MineArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    // two stage buffers, each: W rows then Z rows
+    unsigned char* stage0 = smem;
+    constexpr int kStageBuf = (kBM + kBN) * kRowStride;
+    float* tau = reinterpret_cast<float*>(smem + 2 * kStageBuf);
+    int* cnt = reinterpret_cast<int*>(tau + kBN);
+    int* hist = cnt + kBN;                                   // [kMineWaves][256]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave & 1;          // which 64-label half
-    const int wn = wave >> 1;         // which 64-query half
-    const int slice = blockIdx.x % S;
-    const int64_t qtile = blockIdx.x / S;
-    const int64_t q0 = qtile * kBN;
-    const int64_t row_bytes = static_cast<int64_t>(d) * sizeof(T);
-    const int nkb = static_cast<int>((row_bytes + kStageBytes - 1) / kStageBytes);
-    const int64_t nLT = (L + kBM - 1) / kBM;
-    const int64_t t_begin = static_cast<int64_t>(slice) * tiles_per_slice;
-    int64_t t_end = t_begin + tiles_per_slice;
-    t_end = t_end < nLT ? t_end : nLT;
+    const int wm = wave & 1;          // which 128-label half
+    const int wn = wave >> 1;         // which 64-query quarter
+    uint64_t* my_lists = a.lists + static_cast<size_t>(blockIdx.x) * kBN * kCandCap;
 
-    uint64_t* my_cand = cand + static_cast<size_t>(blockIdx.x) * kBN * kCandCap;
-    const unsigned char* Zb = reinterpret_cast<const unsigned char*>(Z);
-    const unsigned char* Wb = reinterpret_cast<const unsigned char*>(W);
+    // ---- which (query tile, label slice) items this workgroup processes
+    int64_t item, item_step, item_end;
+    int slice_fixed = -1;
+    if (a.Qx > 0) {                   // slices bound to XCDs: workgroup w runs on XCD w % 8
+        const int xcd = blockIdx.x % kXcds;
+        const int cu = blockIdx.x / kXcds;
+        slice_fixed = xcd + kXcds * (cu / a.Qx);
+        item = cu % a.Qx; item_step = a.Qx; item_end = a.nQT;        // items are query tiles
+        if (slice_fixed >= a.S) item_end = 0;
+    } else {
+        item = blockIdx.x; item_step = kMineGrid; item_end = a.nQT * a.S;
+    }
 
-    if (tid < kBN) { tau[tid] = -INFINITY; cnt[tid] = 0; }
-    __syncthreads();
+    const int row = tid >> 3;
+    const uint32_t kcol = (tid & 7) * 16;
+    // LDS addresses of this thread's fragments and stage chunks
+    const int frag_a = (wm * 128 + (lane & 31)) * kRowStride + (lane >> 5) * 16;
+    const int frag_b = kBM * kRowStride + (wn * 64 + (lane & 31)) * kRowStride + (lane >> 5) * 16;
+    const int st_off = row * kRowStride + static_cast<int>(kcol);
 
-    for (int64_t lt = t_begin; lt < t_end; ++lt) {
-        const int64_t l0 = lt * kBM;
-        f32x16 acc[2][2];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+    for (; item < item_end; item += item_step) {
+        const int64_t qtile = a.Qx > 0 ? item : item / a.S;
+        const int slice = a.Qx > 0 ? slice_fixed : static_cast<int>(item % a.S);
+        const int64_t t_begin = a.tile_lo + static_cast<int64_t>(slice) * a.tiles_per_slice;
+        int64_t t_end = t_begin + a.tiles_per_slice;
+        t_end = t_end < a.tile_hi ? t_end : a.tile_hi;
+        if (t_end <= t_begin) continue;                      // uniform: an empty slice
+        const int64_t q0 = qtile * kBN;
+        if (tid < kBN) { tau[tid] = ordered_to_float(a.tau_g[q0 + tid]); cnt[tid] = 0; }
 
-        uint4 rw[4], rz[4];
-        load_stage(Wb, l0, L, row_bytes, 0, rw);
-        load_stage(Zb, q0, Zq, row_bytes, 0, rz);
-        for (int kb = 0; kb < nkb; ++kb) {
-            __syncthreads();                       // previous stage fully consumed
-            store_stage(ldsW, rw);
-            store_stage(ldsZ, rz);
-            __syncthreads();
-            if (kb + 1 < nkb) {                    // next stage in flight during the MFMAs
-                load_stage(Wb, l0, L, row_bytes, (kb + 1) * kStageBytes, rw);
-                load_stage(Zb, q0, Zq, row_bytes, (kb + 1) * kStageBytes, rz);
-            }
+        // byte offsets of this thread's four Z rows (rows past the end repeat the last row)
+        const unsigned char* zbase = a.Z + q0 * a.row_bytes;
+        uint32_t zoff[4];
+        {
+            const int64_t zlast = a.Zq - 1 - q0;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                uint4 a[2], b[2];
-                const int koff = kk * 32 + (lane >> 5) * 16;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-                    a[mt] = *reinterpret_cast<const uint4*>(
-                        ldsW + (wm * 64 + mt * 32 + (lane & 31)) * kRowStride + koff);
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    b[nt] = *reinterpret_cast<const uint4*>(
-                        ldsZ + (wn * 64 + nt * 32 + (lane & 31)) * kRowStride + koff);
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt) MineTraits<T>::mma(a[mt], b[nt], acc[mt][nt]);
+            for (int it = 0; it < 4; ++it) {
+                const int64_t r = row + 64 * it;
+                zoff[it] = static_cast<uint32_t>((r < zlast ? r : zlast) * a.row_bytes) + kcol;
             }
         }
 
-        // ---- threshold filter: lane owns query column (lane & 31) of each N tile
+        // ---- the load stream runs two stages ahead of the compute stream and stops at the last stage
+        int64_t ld_tile = t_begin;
+        int ld_kb = 0;
+        StageRegs regs;
+        bool regs_ok = true;          // KTAIL: chunk lies inside the row
+        auto load_next = [&]() {
+            const int64_t l0 = ld_tile * kBM;
+            const unsigned char* wbase = a.W + l0 * a.row_bytes;
+            const int64_t wlast = a.L - 1 - l0;
+            uint32_t kb = static_cast<uint32_t>(ld_kb) * kStageBytes;
+            if (KTAIL) {
+                regs_ok = kb + kcol < static_cast<uint32_t>(a.row_bytes);
+                kb = regs_ok ? kb : 0u;                  // any valid address; the value is dropped
+            }
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int qloc = wn * 64 + nt * 32 + (lane & 31);
-            const float t = tau[qloc];
-            const bool qok = (q0 + qloc) < Zq;
-            uint64_t* list = my_cand + static_cast<size_t>(qloc) * kCandCap;
+            for (int it = 0; it < 4; ++it) {
+                const int64_t r = row + 64 * it;
+                const uint32_t woff = static_cast<uint32_t>((r < wlast ? r : wlast) * a.row_bytes) + kcol;
+                regs.w[it] = *reinterpret_cast<const uint4*>(wbase + (woff + kb));
+                regs.z[it] = *reinterpret_cast<const uint4*>(zbase + (zoff[it] + kb));
+            }
+            if (++ld_kb == a.nkb) { ld_kb = 0; if (ld_tile + 1 < t_end) ++ld_tile; }
+        };
+        auto store_regs = [&](unsigned char* buf) {
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
+            for (int it = 0; it < 4; ++it) {
+                uint4 w = regs.w[it], z = regs.z[it];
+                if (KTAIL && !regs_ok) { w = make_uint4(0, 0, 0, 0); z = make_uint4(0, 0, 0, 0); }
+                *reinterpret_cast<uint4*>(buf + st_off + 64 * it * kRowStride) = w;
+                *reinterpret_cast<uint4*>(buf + kBM * kRowStride + st_off + 64 * it * kRowStride) = z;
+            }
+        };
+
+        f32x16 acc[4][2];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int64_t lab = l0 + wm * 64 + mt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-                    const float v = acc[mt][nt][i] + 0.0f;     // -0 -> +0
-                    if (qok && lab < L && v >= t) {
-                        const int slot = atomicAdd(&cnt[qloc], 1);
-                        list[slot] = make_key(v, static_cast<int32_t>(lab));
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int n = 0; n < 2; ++n)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.0f;
+
+        load_next();
+        __syncthreads();                                     // tau/cnt visible; LDS free
+        store_regs(stage0);
+        load_next();
+        __syncthreads();
+
+        int buf_sel = 0;
+        for (int64_t tile = t_begin; tile < t_end; ++tile) {
+            for (int kb = 0; kb < a.nkb; ++kb) {
+                const unsigned char* cur = stage0 + buf_sel * kStageBuf;
+                buf_sel ^= 1;
+                // the other buffer was last read before the barrier that ended the previous stage
+                store_regs(stage0 + buf_sel * kStageBuf);
+                __builtin_amdgcn_sched_barrier(0);           // keep the global loads of stage s+2 ahead
+                load_next();                                 // of this stage's MFMAs: they need its whole
+                __builtin_amdgcn_sched_barrier(0);           // duration to arrive
+
+                uint4 fa[2][4], fb[2][2];
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+                    fa[0][mt] = *reinterpret_cast<const uint4*>(cur + frag_a + mt * 32 * kRowStride);
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    fb[0][nt] = *reinterpret_cast<const uint4*>(cur + frag_b + nt * 32 * kRowStride);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    if (kk < 3) {                            // fragments of the next K sub-step
+#pragma unroll
+                        for (int mt = 0; mt < 4; ++mt)
+                            fa[(kk + 1) & 1][mt] = *reinterpret_cast<const uint4*>(
+                                cur + frag_a + mt * 32 * kRowStride + (kk + 1) * 32);
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt)
+                            fb[(kk + 1) & 1][nt] = *reinterpret_cast<const uint4*>(
+                                cur + frag_b + nt * 32 * kRowStride + (kk + 1) * 32);
+                    }
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt)
+                            MineTraits<T>::mma(fa[kk & 1][mt], fb[kk & 1][nt], acc[mt][nt]);
+                }
+                if (kb + 1 < a.nkb) __syncthreads();
+            }
+
+            // ---- threshold filter: lane owns query column (lane & 31) of each N tile
+            const int64_t l0 = tile * kBM;
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const int qloc = wn * 64 + nt * 32 + (lane & 31);
+                const float t = tau[qloc];
+                const bool qok = (q0 + qloc) < a.Zq;
+                float mx = acc[0][nt][0];
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[mt][nt][i]);
+                if (__ballot(qok && mx >= t) != 0ull) {
+                    uint64_t* list = my_lists + static_cast<size_t>(qloc) * kCandCap;
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int64_t lab = l0 + wm * 128 + mt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                            const float v = acc[mt][nt][i] + 0.0f;     // -0 -> +0
+                            if (qok && lab < a.L && v >= t) {
+                                const int slot = atomicAdd(&cnt[qloc], 1);
+                                list[slot] = make_key(v, static_cast<int32_t>(lab));
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.0f;
+            }
+            __syncthreads();
+
+            // ---- wave w looks after queries 32w..32w+31.  A list that could overflow during the
+            // next tile (or, at the end of the slice, exceeds what a slice may append) is cut to
+            // its best k and tau rises for the rest of the slice.
+            {
+                const bool last = (tile + 1 == t_end);
+                const int qloc = wave * 32 + (lane & 31);
+                const bool qok = (q0 + qloc) < a.Zq;
+                int n = cnt[qloc];
+                const bool want = lane < 32 && qok && (last ? n > a.append_max : n > kCandCap - kBM);
+                uint64_t todo = __ballot(want);
+                if (todo != 0ull || last) {
+                    float t_new = -INFINITY;
+                    while (todo) {
+                        const int src = __ffsll(static_cast<long long>(todo)) - 1;
+                        todo &= todo - 1;
+                        const int qsel = wave * 32 + src;
+                        const int nsel = __shfl(n, src, kWave);
+                        const float t = wave_select_k<kCandCap / kWave>(
+                            my_lists + static_cast<size_t>(qsel) * kCandCap, nsel, a.k, hist + wave * 256);
+                        if (lane == src) { t_new = t; n = a.k; }
+                    }
+                    if (want) { tau[qloc] = fmaxf(tau[qloc], t_new); cnt[qloc] = n; }
+                    if (last) {
+                        // ---- close the slice: append the survivors to the global list of each query
+                        int base = 0;
+                        if (lane < 32 && qok && n > 0) base = atomicAdd(&a.gcnt[q0 + qloc], n);
+                        uint64_t some = __ballot(lane < 32 && qok && n > 0);
+                        while (some) {
+                            const int src = __ffsll(static_cast<long long>(some)) - 1;
+                            some &= some - 1;
+                            const int nsel = __shfl(n, src, kWave);
+                            const int bsel = __shfl(base, src, kWave);
+                            const int qsel = wave * 32 + src;
+                            const uint64_t* list = my_lists + static_cast<size_t>(qsel) * kCandCap;
+                            uint64_t* out = a.glist + static_cast<size_t>(q0 + qsel) * a.glist_cap;
+                            for (int e = lane; e < nsel; e += kWave)
+                                if (bsel + e < a.glist_cap) out[bsel + e] = list[e];
+                        }
                     }
                 }
             }
-        }
-        __syncthreads();
-        // ---- lists that could overflow during the next tile are reduced now
-        for (int q = wave; q < kBN; q += kMineThreads / kWave) {
-            const int n = cnt[q];
-            if (n > kCandCap - kBM) {
-                const float t = wave_select_k(my_cand + static_cast<size_t>(q) * kCandCap, n, k, hist[wave]);
-                if (lane == 0) { tau[q] = t; cnt[q] = k; }
-            }
-        }
-        // the barrier at the top of the next K loop orders these updates
-    }
-
-    __syncthreads();
-    // ---- close the slice: at most k keys per query, padded to kcap
-    for (int q = wave; q < kBN; q += kMineThreads / kWave) {
-        int n = cnt[q];
-        uint64_t* list = my_cand + static_cast<size_t>(q) * kCandCap;
-        if (n > k) {
-            wave_select_k(list, n, k, hist[wave]);
-            n = k;
-        }
-        for (int e = n + lane; e < kcap; e += kWave) list[e] = kKeySentinel;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Merge the S per-slice lists of one query and write the k best, sorted.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256)
-void mine_merge_kernel(const uint64_t* __restrict__ cand, int S, int kcap, int k, int n2,
-                       int32_t* __restrict__ shortlist, float* __restrict__ scores) {
-    __shared__ uint64_t keys[kMergeMax];
-    const int64_t q = blockIdx.x;
-    const int64_t qtile = q / kBN;
-    const int qloc = static_cast<int>(q % kBN);
-    const int total = S * kcap;
-    for (int idx = threadIdx.x; idx < n2; idx += blockDim.x) {
-        uint64_t v = kKeySentinel;
-        if (idx < total) {
-            const int s = idx / kcap, e = idx % kcap;
-            v = cand[((static_cast<size_t>(qtile) * S + s) * kBN + qloc) * kCandCap + e];
-        }
-        keys[idx] = v;
-    }
-    __syncthreads();
-    for (int size = 2; size <= n2; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int t = threadIdx.x; t < n2 / 2; t += blockDim.x) {
-                const int lo = 2 * t - (t & (stride - 1));
-                const int hi = lo + stride;
-                const bool up = (lo & size) == 0;
-                const uint64_t a = keys[lo], b = keys[hi];
-                if ((a > b) == up) { keys[lo] = b; keys[hi] = a; }
-            }
             __syncthreads();
         }
     }
-    for (int r = threadIdx.x; r < k; r += blockDim.x) {
-        const uint64_t v = keys[r];
-        const int32_t id = key_id(v);
-        shortlist[q * k + r] = id;
+}
+
+__global__ void mine_init_kernel(uint32_t* tau_g, int32_t* gcnt, int64_t n) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) { tau_g[i] = kTauInit; gcnt[i] = 0; }
+}
+
+// ---------------------------------------------------------------------------
+// Radix select for lists too long for registers (n > 64*kSelectRegs): the keys
+// are streamed from memory in every pass.  Same result as wave_select_k.
+// ---------------------------------------------------------------------------
+__device__ __noinline__ float wave_select_stream(uint64_t* __restrict__ buf, int n, int k, int* hist) {
+    const int lane = lane_id();
+    uint64_t prefix = 0, pmask = 0;
+    int need = k;
+    for (int pass = 0; pass < 8; ++pass) {
+        const int shift = 56 - 8 * pass;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) hist[lane * 4 + j] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        for (int idx = lane; idx < n; idx += kWave) {
+            const uint64_t key = buf[idx];
+            if ((key & pmask) == prefix) atomicAdd(&hist[static_cast<int>((key >> shift) & 255u)], 1);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        int c[4];
+        int s = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { c[j] = hist[lane * 4 + j]; s += c[j]; }
+        const int incl = wave_incl_scan(s);
+        const int excl = incl - s;
+        const bool mine = (excl < need) && (need <= incl);
+        int dsel = 0, needn = 0, have = 0;
+        if (mine) {
+            int cum = excl;
+            bool done = false;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (!done && need <= cum + c[j]) {
+                    dsel = lane * 4 + j; needn = need - cum; have = c[j]; done = true;
+                }
+                cum += c[j];
+            }
+        }
+        const uint64_t bal = __ballot(mine);
+        const int src = __ffsll(static_cast<long long>(bal)) - 1;
+        dsel = __shfl(dsel, src, kWave);
+        needn = __shfl(needn, src, kWave);
+        have = __shfl(have, src, kWave);
+        prefix |= static_cast<uint64_t>(dsel) << shift;
+        pmask |= 0xffull << shift;
+        need = needn;
+        if (have == need) break;
+    }
+    const uint64_t bound = prefix | ~pmask;
+    // compaction in place: a chunk is read into registers before anything of it is
+    // overwritten, and the write position never passes the read position
+    uint64_t kmax = 0;
+    int base = 0;
+    for (int c0 = 0; c0 < n; c0 += kWave) {
+        const int idx = c0 + lane;
+        const uint64_t key = idx < n ? buf[idx] : kKeySentinel;
+        const bool sel = idx < n && key <= bound;
+        const uint64_t m = __ballot(sel);
+        const int p = base + __popcll(m & lanemask_lt());
+        if (sel && p < k) {
+            buf[p] = key;
+            kmax = key > kmax ? key : kmax;
+        }
+        base += __popcll(m);
+    }
+    kmax = wave_max_u64(kmax);
+    return key_score(kmax);
+}
+
+// ---------------------------------------------------------------------------
+// After a phase: one wave per query cuts the global candidate list to its best
+// k and publishes the k-th score as the threshold of the next phase.  After the
+// last phase the winners are sorted and written out.
+// ---------------------------------------------------------------------------
+constexpr int kSelectWaves = 4;
+
+__global__ __launch_bounds__(kSelectWaves * kWave)
+void mine_select_kernel(uint64_t* __restrict__ glist, int32_t* __restrict__ gcnt,
+                        uint32_t* __restrict__ tau_g, int64_t Zq, int glist_cap, int k, int final_phase,
+                        int32_t* __restrict__ shortlist, float* __restrict__ scores) {
+    __shared__ int hist[kSelectWaves][256];
+    __shared__ uint64_t sorted[kSelectWaves][XC_MAX_K_MINE];
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * kSelectWaves + wave;
+    if (q >= Zq) return;                               // wave-uniform; no workgroup barrier below
+    uint64_t* list = glist + static_cast<size_t>(q) * glist_cap;
+    int n = gcnt[q];
+    n = n < glist_cap ? n : glist_cap;
+    if (n > k) {
+        const float t = (n <= kSelectRegs * kWave) ? wave_select_k<kSelectRegs>(list, n, k, hist[wave])
+                                                   : wave_select_stream(list, n, k, hist[wave]);
+        n = k;
+        if (lane == 0) { gcnt[q] = k; tau_g[q] = float_to_ordered(t); }
+    }
+    if (!final_phase) return;
+    // bitonic sort of the (at most 128) winners inside the wave
+    uint64_t* srt = sorted[wave];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // the select's stores to `list` are visible
+    for (int e = lane; e < XC_MAX_K_MINE; e += kWave) srt[e] = e < n ? list[e] : kKeySentinel;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    for (int size = 2; size <= XC_MAX_K_MINE; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            const int t = lane;                       // 64 compare-exchanges cover 128 keys
+            const int lo = 2 * t - (t & (stride - 1));
+            const int hi = lo + stride;
+            const bool up = (lo & size) == 0;
+            const uint64_t x = srt[lo], y = srt[hi];
+            if ((x > y) == up) { srt[lo] = y; srt[hi] = x; }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        }
+    }
+    for (int r = lane; r < k; r += kWave) {
+        const uint64_t v = srt[r];
+        shortlist[q * k + r] = key_id(v);
         if (scores) scores[q * k + r] = (v == kKeySentinel) ? -INFINITY : key_score(v);
     }
 }
@@ -317,35 +517,36 @@ void mine_merge_kernel(const uint64_t* __restrict__ cand, int S, int kcap, int k
 // ---------------------------------------------------------------------------
 struct MinePlan {
     int64_t nQT, nLT;
-    int S, tiles_per_slice, kcap, n2;
-    size_t ws_bytes;
+    int kcap, nkb, glist_cap;
+    size_t off_lists, off_glist, off_gcnt, off_tau, ws_bytes;
+    size_t lds_tile;
 };
+
+static int slices_cap(int kcap) { return kcap <= 64 ? 64 : 32; }    // slices per phase at most
 
 static int plan_mine(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, MinePlan* p) {
     if (t != XC_F32 && t != XC_BF16) return XC_EINVAL;
     if (Zq < 1 || L < 1 || d < 1 || k_h < 1 || k_h > XC_MAX_K_MINE || k_h > L) return XC_ESHAPE;
     const int64_t row_bytes = static_cast<int64_t>(d) * (t == XC_F32 ? 4 : 2);
-    if (row_bytes % 16 != 0) return XC_ESHAPE;
-    if (L > 0x7fffffffLL) return XC_ESHAPE;
+    if (row_bytes % 16 != 0 || row_bytes > (1 << 20)) return XC_ESHAPE;
+    if (L > 0x7fffffffLL || Zq > 0x7fffffffLL) return XC_ESHAPE;
     int kcap = 8;
     while (kcap < k_h) kcap <<= 1;
     p->kcap = kcap;
+    p->nkb = static_cast<int>((row_bytes + kStageBytes - 1) / kStageBytes);
     p->nQT = (Zq + kBN - 1) / kBN;
     p->nLT = (L + kBM - 1) / kBM;
-    int64_t S = (1024 + p->nQT - 1) / p->nQT;           // aim for >= ~1024 workgroups
-    const int64_t s_max = kMergeMax / kcap;
-    if (S > s_max) S = s_max;
-    if (S > p->nLT) S = p->nLT;
-    if (S < 1) S = 1;
-    const int64_t tps = (p->nLT + S - 1) / S;
-    S = (p->nLT + tps - 1) / tps;                        // no empty slice
-    if (tps > 0x7fffffffLL || p->nQT * S > 0x7fffffffLL) return XC_ESHAPE;
-    p->S = static_cast<int>(S);
-    p->tiles_per_slice = static_cast<int>(tps);
-    int n2 = 2;
-    while (n2 < p->S * kcap) n2 <<= 1;
-    p->n2 = n2;
-    p->ws_bytes = static_cast<size_t>(p->nQT) * p->S * kBN * kCandCap * sizeof(uint64_t);
+    // a phase appends at most kcap keys per slice to a list that holds at most k keys
+    p->glist_cap = kcap * (slices_cap(kcap) + 1);
+    size_t off = 0;
+    auto take = [&off](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
+    const size_t nq = static_cast<size_t>(p->nQT) * kBN;
+    p->off_lists = take(static_cast<size_t>(kMineGrid) * kBN * kCandCap * sizeof(uint64_t));
+    p->off_glist = take(nq * p->glist_cap * sizeof(uint64_t));
+    p->off_gcnt = take(nq * sizeof(int32_t));
+    p->off_tau = take(nq * sizeof(uint32_t));
+    p->ws_bytes = off;
+    p->lds_tile = 2 * static_cast<size_t>(kBM + kBN) * kRowStride + kBN * 8 + kMineWaves * 256 * 4;
     return XC_OK;
 }
 
@@ -371,20 +572,72 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
     if (!aligned16(Z) || !aligned16(W) || !aligned16(ws)) return XC_EINVAL;
     if (ws_bytes < p.ws_bytes) return XC_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const dim3 grid(static_cast<unsigned>(p.nQT * p.S));
-    uint64_t* cand = static_cast<uint64_t*>(ws);
-    if (t == XC_BF16) {
-        XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t><<<grid, kMineThreads, 0, st>>>(
-            static_cast<const bf16_t*>(Z), static_cast<const bf16_t*>(W), Zq, L, d, k_h, p.kcap, p.S,
-            p.tiles_per_slice, cand)));
-    } else {
-        XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<float><<<grid, kMineThreads, 0, st>>>(
-            static_cast<const float*>(Z), static_cast<const float*>(W), Zq, L, d, k_h, p.kcap, p.S,
-            p.tiles_per_slice, cand)));
+    unsigned char* w8 = static_cast<unsigned char*>(ws);
+    MineArgs a;
+    a.Z = static_cast<const unsigned char*>(Z);
+    a.W = static_cast<const unsigned char*>(W);
+    a.Zq = Zq; a.L = L;
+    a.row_bytes = static_cast<int64_t>(d) * (t == XC_F32 ? 4 : 2);
+    a.k = k_h; a.kcap = p.kcap; a.nkb = p.nkb;
+    a.nQT = p.nQT;
+    a.glist_cap = p.glist_cap;
+    a.lists = reinterpret_cast<uint64_t*>(w8 + p.off_lists);
+    a.glist = reinterpret_cast<uint64_t*>(w8 + p.off_glist);
+    a.gcnt = reinterpret_cast<int32_t*>(w8 + p.off_gcnt);
+    uint32_t* tau_g = reinterpret_cast<uint32_t*>(w8 + p.off_tau);
+    a.tau_g = tau_g;
+
+    static bool attr_done = false;       // raise the dynamic LDS limit once per process
+    if (!attr_done) {
+        const void* fns[4] = {reinterpret_cast<const void*>(&mine_tile_kernel<bf16_t, false>),
+                              reinterpret_cast<const void*>(&mine_tile_kernel<bf16_t, true>),
+                              reinterpret_cast<const void*>(&mine_tile_kernel<float, false>),
+                              reinterpret_cast<const void*>(&mine_tile_kernel<float, true>)};
+        for (const void* fn : fns)
+            XC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             static_cast<int>(p.lds_tile)));
+        attr_done = true;
     }
+    const int64_t nq = p.nQT * kBN;
+    mine_init_kernel<<<dim3(static_cast<unsigned>((nq + 255) / 256)), 256, 0, st>>>(tau_g, a.gcnt, nq);
     XC_HIP_CHECK(hipGetLastError());
-    XC_LAUNCH(K_MINE_MERGE, st, (mine_merge_kernel<<<dim3(static_cast<unsigned>(Zq)), 256, 0, st>>>(
-        cand, p.S, p.kcap, k_h, p.n2, shortlist, scores)));
-    XC_HIP_CHECK(hipGetLastError());
+
+    int64_t lo = 0;
+    while (lo < p.nLT) {
+        // phase sizes 1, 7, 56, ... tiles: each phase sees 8x the labels seen before it
+        int64_t hi = lo == 0 ? 1 : lo * kPhaseGrowth;
+        if (hi > p.nLT || p.nLT - hi < hi / 4) hi = p.nLT;      // fold a short remainder into this phase
+        const int64_t nT = hi - lo;
+        if (nT >= kXcds) {
+            // slices per XCD: as many as the phase supports, so that few query tiles are in
+            // flight per XCD and their Z rows stay in that XCD's L2
+            int Sx = 8;
+            while (Sx > 1 && (nT < static_cast<int64_t>(kXcds) * Sx || kXcds * Sx > slices_cap(p.kcap))) Sx >>= 1;
+            a.S = kXcds * Sx;
+            a.Qx = kCusPerXcd / Sx;
+        } else {                                           // a few tiles: one slice per tile, plain order
+            a.S = static_cast<int>(nT);
+            a.Qx = 0;
+        }
+        a.tile_lo = lo; a.tile_hi = hi;
+        a.tiles_per_slice = (nT + a.S - 1) / a.S;
+        a.append_max = (p.glist_cap - p.kcap) / a.S;
+        if (a.append_max > kCandCap) a.append_max = kCandCap;
+        const bool ktail = (a.row_bytes % kStageBytes) != 0;
+        if (t == XC_BF16) {
+            if (ktail) XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t, true><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));
+            else XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t, false><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));
+        } else {
+            if (ktail) XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<float, true><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));
+            else XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<float, false><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));
+        }
+        XC_HIP_CHECK(hipGetLastError());
+        const int final_phase = hi == p.nLT ? 1 : 0;
+        XC_LAUNCH(K_MINE_SELECT, st, (mine_select_kernel<<<dim3(static_cast<unsigned>((Zq + kSelectWaves - 1) / kSelectWaves)),
+                                                          kSelectWaves * kWave, 0, st>>>(
+            a.glist, a.gcnt, tau_g, Zq, p.glist_cap, k_h, final_phase, shortlist, scores)));
+        XC_HIP_CHECK(hipGetLastError());
+        lo = hi;
+    }
     return XC_OK;
 }
