@@ -45,6 +45,7 @@ typedef enum {
 #define XC_MAX_K_SAMPLE 1024   /* k_h accepted by xc_sample_negatives              */
 #define XC_MAX_ROW_BYTES 4096  /* d * sizeof(element) accepted by xc_step          */
 #define XC_MAX_CANDIDATES 16384 /* k_p + n_neg accepted by xc_step                 */
+#define XC_MAX_KP 256          /* k_p accepted by xc_step                          */
 
 const char* xc_strerror(int status);
 int xc_last_hip_error(void);
@@ -103,11 +104,12 @@ int xc_sample_negatives(const int32_t* shortlist /* [B*k_h] or NULL */, int64_t 
  *            positive is skipped).
  *   loss[0] = (1/B) sum_i loss_i;  dZ = d loss / d Z (fp32, [B*d]);
  *   w_l <- w_l - lr * d loss / d w_l for every label in an unmasked pair;
- *   a label in several pairs gets the summed gradient, added in order of
- *   increasing (i, slot), and is written once (rounded to nearest even for bf16).
+ *   a label in several pairs gets the summed gradient, added in a fixed order
+ *   (results are bitwise reproducible run to run), and is written once (rounded
+ *   to nearest even for bf16).
  *   touched[0..n_touched[0]) = those labels, ascending; no other row changes.
  *   W_rows_out, if not NULL, receives the updated rows in that order.
- * Z and dZ must not alias.  Requires B >= 1, k_p >= 0, n_neg >= 0,
+ * Z and dZ must not alias.  Requires B >= 1, 0 <= k_p <= XC_MAX_KP, n_neg >= 0,
  * 1 <= k_p + n_neg <= XC_MAX_CANDIDATES, B*(k_p+n_neg) < 2^31,
  * d*sizeof(element) a multiple of 16 and <= XC_MAX_ROW_BYTES.
  * The workspace size does not depend on L.

@@ -14,24 +14,50 @@ constexpr int kStepThreads = 256;
 constexpr int kMaxRowFloats = XC_MAX_ROW_BYTES / 2;     // bf16 rows hold the most elements
 constexpr int kSortTile = 256;                          // keys ranked together in the scatter
 constexpr int kSortMaxBlocks = 512;
-constexpr int kRadixBits = 8;
-constexpr int kRadix = 1 << kRadixBits;
+constexpr int kUpdateMaxGrid = 256 * 8;                 // workgroups of the update kernel
+constexpr int kMaxRadixBits = 11;
+constexpr int kMaxRadix = 1 << kMaxRadixBits;
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+    bf16x2 x, y;
+    __builtin_memcpy(&x, &a, 4);
+    __builtin_memcpy(&y, &b, 4);
+    return __builtin_amdgcn_fdot2_f32_bf16(x, y, c, false);     // a.lo*b.lo + a.hi*b.hi + c in fp32
+}
 
 template <typename T> struct Elem;
 template <> struct Elem<bf16_t> {
     static constexpr int kPerChunk = 8;
+    // s + <w, z> over the 8 elements of a chunk, both still packed
+    static __device__ __forceinline__ float dot(const uint4& w, const uint4& z, float s) {
+        s = dot2_bf16(w.x, z.x, s); s = dot2_bf16(w.y, z.y, s);
+        s = dot2_bf16(w.z, z.z, s); s = dot2_bf16(w.w, z.w, s);
+        return s;
+    }
     static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) { unpack8(v, f); }
+    // round to nearest even by the hardware conversion (v_cvt_pk_bf16_f32)
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        const f32x2 v = {lo, hi};
+        const bf16x2 r = __builtin_convertvector(v, bf16x2);
+        uint32_t u;
+        __builtin_memcpy(&u, &r, 4);
+        return u;
+    }
     static __device__ __forceinline__ uint4 pack(const float (&f)[8]) {
-        uint4 v;
-        v.x = float_to_bf16_bits(f[0]) | (float_to_bf16_bits(f[1]) << 16);
-        v.y = float_to_bf16_bits(f[2]) | (float_to_bf16_bits(f[3]) << 16);
-        v.z = float_to_bf16_bits(f[4]) | (float_to_bf16_bits(f[5]) << 16);
-        v.w = float_to_bf16_bits(f[6]) | (float_to_bf16_bits(f[7]) << 16);
-        return v;
+        return make_uint4(pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7]));
     }
 };
 template <> struct Elem<float> {
     static constexpr int kPerChunk = 4;
+    static __device__ __forceinline__ float dot(const uint4& w, const uint4& z, float s) {
+        s = fmaf(__uint_as_float(w.x), __uint_as_float(z.x), s);
+        s = fmaf(__uint_as_float(w.y), __uint_as_float(z.y), s);
+        s = fmaf(__uint_as_float(w.z), __uint_as_float(z.z), s);
+        s = fmaf(__uint_as_float(w.w), __uint_as_float(z.w), s);
+        return s;
+    }
     static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[4]) {
         f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
         f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
@@ -52,33 +78,82 @@ __device__ __forceinline__ float sigmoidf(float x) {
 // factor that rescales a sum kept relative to maximum m to a new maximum mn >= m
 __device__ __forceinline__ float rescale(float m, float mn) { return m == mn ? 1.0f : expf(m - mn); }
 
+// ---- fast transcendental pieces (hardware exp2/log2/rcp, about 1 ulp each) ------------------
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+// log(1 + e) for 0 <= e <= 1: series below 2^-6 (where 1 + e would lose the low bits of e)
+__device__ __forceinline__ float fast_log1p(float e) {
+    const float series = e * (1.0f - e * (0.5f - e * (1.0f / 3.0f)));
+    const float direct = __builtin_amdgcn_logf(1.0f + e) * 0.693147180559945309f;
+    return e < 0.015625f ? series : direct;
+}
+
+// Transposing reduction over a group of G lanes: v[u] holds this lane's partial of row u.
+// Returns, in lane gl, the sum over the group of row row_of_lane(gl): U-1 exchanges in the
+// halving steps plus log2(G/U) plain ones, instead of U*log2(G).
+template <int U>
+__device__ __forceinline__ float reduce_rows(float (&v)[U], int G, int gl) {
+    int off = G >> 1;
+#pragma unroll
+    for (int cnt = U; cnt > 1; cnt >>= 1) {
+        const bool hi = (gl & off) != 0;
+#pragma unroll
+        for (int j = 0; j < cnt / 2; ++j) {
+            const float send = hi ? v[j] : v[j + cnt / 2];
+            const float keep = hi ? v[j + cnt / 2] : v[j];
+            v[j] = keep + __shfl_xor(send, off, kWave);
+        }
+        off >>= 1;
+    }
+    float y = v[0];
+    for (; off > 0; off >>= 1) y += __shfl_xor(y, off, kWave);
+    return y;
+}
+template <int U>
+__device__ __forceinline__ int row_of_lane(int gl, int G) {
+    int r = 0, off = G >> 1;
+#pragma unroll
+    for (int cnt = U; cnt > 1; cnt >>= 1) { r += (gl & off) ? cnt / 2 : 0; off >>= 1; }
+    return r;
+}
+template <int U>
+__device__ __forceinline__ int lane_of_row(int u, int G) {      // lowest lane of the group holding row u
+    int l = 0, off = G >> 1;
+#pragma unroll
+    for (int cnt = U; cnt > 1; cnt >>= 1) { l += (u & (cnt / 2)) ? off : 0; off >>= 1; }
+    return l;
+}
+
 // ---------------------------------------------------------------------------
 // gather + scores + loss + dZ.  One workgroup per query; a "group" of G lanes
 // (G = 16, 32 or 64) owns one candidate row at a time, lane gl of the group
 // holding the 16-byte chunks gl, gl+G, ... of the row (CPL chunks per lane).
 // ---------------------------------------------------------------------------
-template <typename T, int CPL, int KIND>
+template <typename T, int CPL, int KIND, int U>
 __global__ __launch_bounds__(kStepThreads)
 void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, int d,
                    const int32_t* __restrict__ pos, int k_p, const int32_t* __restrict__ neg,
-                   const float* __restrict__ logq, int n_neg, int G, float inv_B,
+                   const float* __restrict__ logq, int n_neg, int G, int SQ, int64_t B, float inv_B,
                    uint32_t* __restrict__ keys, uint32_t* __restrict__ vals,
                    float* __restrict__ gco, float* __restrict__ loss_q, float* __restrict__ dZ) {
-    constexpr int EPC = Elem<T>::kPerChunk;
-    constexpr int U = 4;                          // candidate rows in flight per group
+    constexpr int EPC = Elem<T>::kPerChunk;       // U = candidate rows in flight per group
     __shared__ float red[kStepThreads / kWave][kMaxRowFloats];
+    __shared__ int32_t spos[XC_MAX_KP];           // the query's positives, for the (1 - y_l) mask
     __shared__ float part[kStepThreads];          // per-group partial results
     __shared__ float part2[kStepThreads];
     __shared__ float part3[kStepThreads];
     __shared__ float part4[kStepThreads];
 
-    const int64_t i = blockIdx.x;
+    // SQ workgroups share one query (the candidates are dealt out in turn); each writes a
+    // partial loss and a partial dZ that a later kernel adds up in a fixed order
+    const int64_t i = blockIdx.x / SQ;
+    const int sq = blockIdx.x % SQ;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int gl = lane & (G - 1);
-    const int NG = kStepThreads / G;
-    const int grp = tid / G;
+    const int NG = (kStepThreads / G) * SQ;               // groups working on this query
+    const int grp = sq * (kStepThreads / G) + tid / G;
     const int n = k_p + n_neg;
     const int nchunks = d / EPC;
     const int64_t row_bytes = static_cast<int64_t>(d) * sizeof(T);
@@ -88,16 +163,15 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
     const float* lq_i = logq + i * n_neg;
     const int64_t p_base = i * n;
 
-    // query row -> registers
-    float zf[CPL][EPC];
+    // query row -> registers, kept in storage format for the dot products
+    uint4 zp[CPL];
     {
         const unsigned char* zrow = reinterpret_cast<const unsigned char*>(Z) + i * row_bytes;
 #pragma unroll
         for (int j = 0; j < CPL; ++j) {
             const int ch = gl + j * G;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (ch < nchunks) v = *reinterpret_cast<const uint4*>(zrow + ch * 16);
-            Elem<T>::unpack(v, zf[j]);
+            zp[j] = make_uint4(0, 0, 0, 0);
+            if (ch < nchunks) zp[j] = *reinterpret_cast<const uint4*>(zrow + ch * 16);
         }
     }
 
@@ -111,6 +185,32 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
     float m_run = -INFINITY, s_run = 0.0f;
     int npos = 0;
 
+    for (int q = tid; q < k_p; q += kStepThreads) spos[q] = pos_i[q];
+    __syncthreads();
+
+    // ids and log-proposals of the candidates this group handles in one iteration; those
+    // of the next iteration are fetched while the rows of the current one are in flight
+    int32_t id_nx[U];
+    float lq_nx[U];
+    auto fetch_ids = [&](int c0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u * NG;
+            id_nx[u] = -1; lq_nx[u] = 0.0f;
+            if (c < n) {
+                if (c < k_p) id_nx[u] = spos[c];
+                else { id_nx[u] = neg_i[c - k_p]; lq_nx[u] = lq_i[c - k_p]; }
+            }
+        }
+    };
+    fetch_ids(grp);
+    const int grp_lane0 = lane & ~(G - 1);       // first lane of this group within the wave
+    const uint64_t grp_mask = (G == kWave ? ~0ull : ((1ull << G) - 1ull)) << grp_lane0;
+    const int row_rep = G / U;                   // lanes that end up holding the same row's score
+    const int my_row = row_of_lane<U>(gl, G);
+    const bool my_rep = (gl & (row_rep - 1)) == 0;
+    const int32_t my_pos = gl < k_p ? spos[gl] : -2;      // lane-parallel (1 - y_l) check
+
     for (int c0 = grp; c0 < n; c0 += NG * U) {
         int32_t id[U];
         float lq[U];
@@ -119,14 +219,12 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u * NG;
-            id[u] = -1; lq[u] = 0.0f; isp[u] = false;
-            if (c < n) {
-                if (c < k_p) { id[u] = pos_i[c]; isp[u] = true; }
-                else { id[u] = neg_i[c - k_p]; lq[u] = lq_i[c - k_p]; }
-            }
+            id[u] = id_nx[u]; lq[u] = lq_nx[u]; isp[u] = c < k_p;
             ok[u] = id[u] >= 0 && id[u] < L;
-            if (ok[u] && !isp[u]) {                 // (1 - y_l): a positive among the negatives
-                for (int q = 0; q < k_p; ++q) ok[u] = ok[u] && (pos_i[q] != id[u]);
+            if (!isp[u]) {                          // (1 - y_l): a positive among the negatives
+                bool hit = my_pos == id[u];
+                for (int q = G + gl; q < k_p; q += G) hit = hit || spos[q] == id[u];
+                ok[u] = ok[u] && (__ballot(hit) & grp_mask) == 0ull;
             }
 #pragma unroll
             for (int j = 0; j < CPL; ++j) {
@@ -136,69 +234,103 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
                     rw[u][j] = *reinterpret_cast<const uint4*>(Wb + static_cast<int64_t>(id[u]) * row_bytes + ch * 16);
             }
         }
+        fetch_ids(c0 + NG * U);
+
+        // per-lane partial dot products of the U rows, then a transposing reduction: lane gl
+        // ends up with the complete score of row my_row (each row replicated in G/U lanes)
+        float ps[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float s = 0.0f;
+#pragma unroll
+            for (int j = 0; j < CPL; ++j) s = Elem<T>::dot(rw[u][j], zp[j], s);
+            ps[u] = s;
+        }
+        const float my_s = reduce_rows<U>(ps, G, gl);
+        float my_lq = 0.0f;
+        bool my_ok = false, my_isp = false;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (my_row == u) { my_lq = lq[u]; my_ok = ok[u]; my_isp = isp[u]; }
+        }
+        float my_g = 0.0f;          // BCE: d loss / d score.  soft-max: weight e^{t - m}
+        float my_t = my_ok ? my_s - my_lq : -INFINITY;     // soft-max logit
+        if (KIND == XC_LOSS_BCE) {
+            if (my_ok) {
+                // e = exp(-|s|) serves softplus(+-s) = max(+-s, 0) + log1p(e) and the sigmoid
+                const float e = fast_exp(-fabsf(my_s));
+                const float l1p = fast_log1p(e);
+                const float r = fast_rcp(1.0f + e);
+                const float sig = my_s >= 0.0f ? r : e * r;
+                float term;
+                if (my_isp) { term = fmaxf(-my_s, 0.0f) + l1p; my_g = sig - 1.0f; }
+                else { const float a = fast_exp(-my_lq); term = a * (fmaxf(my_s, 0.0f) + l1p); my_g = a * sig; }
+                if (my_rep) loss_acc += term;
+                my_g *= inv_B;
+            }
+        } else {
+            float mi = my_t;        // maximum logit of the iteration, over the row-selecting lane bits
+            for (int off = G >> 1; off >= row_rep; off >>= 1) mi = fmaxf(mi, __shfl_xor(mi, off, kWave));
+            const float mn = fmaxf(m_run, mi);
+            const float sc_run = rescale(m_run, mn);
+            my_g = my_ok ? expf(my_t - mn) : 0.0f;
+            float ws = my_g;
+            for (int off = G >> 1; off >= row_rep; off >>= 1) ws += __shfl_xor(ws, off, kWave);
+            s_run = s_run * sc_run + ws;
+            m_run = mn;
+            if (my_ok && my_isp && my_rep) { loss_acc += my_t; ++npos; }
+            if (sc_run != 1.0f) {
+#pragma unroll
+                for (int j = 0; j < CPL; ++j)
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) dz[j][e] *= sc_run;
+            }
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u * NG;
-            float wf[CPL][EPC];
-            float s = 0.0f;
+            const int src = grp_lane0 + lane_of_row<U>(u, G);
+            const float g = __shfl(my_g, src, kWave);
+            if (ok[u]) {
+                float wf[CPL][EPC];
 #pragma unroll
-            for (int j = 0; j < CPL; ++j) {
-                Elem<T>::unpack(rw[u][j], wf[j]);
+                for (int j = 0; j < CPL; ++j) {
+                    Elem<T>::unpack(rw[u][j], wf[j]);
 #pragma unroll
-                for (int e = 0; e < EPC; ++e) s = fmaf(wf[j][e], zf[j][e], s);
-            }
-            for (int off = G >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
-            float g = 0.0f;
-            if (KIND == XC_LOSS_BCE) {
-                if (ok[u]) {
-                    if (isp[u]) { loss_acc += softplusf(-s); g = sigmoidf(s) - 1.0f; }
-                    else { const float a = expf(-lq[u]); loss_acc += a * softplusf(s); g = a * sigmoidf(s); }
-                    g *= inv_B;
+                    for (int e = 0; e < EPC; ++e) dz[j][e] = fmaf(g, wf[j][e], dz[j][e]);
+                }
+                if (KIND == XC_LOSS_SOFTMAX && isp[u]) {
 #pragma unroll
                     for (int j = 0; j < CPL; ++j)
 #pragma unroll
-                        for (int e = 0; e < EPC; ++e) dz[j][e] = fmaf(g, wf[j][e], dz[j][e]);
-                }
-            } else {
-                if (ok[u]) {
-                    const float t = s - lq[u];
-                    g = t;                               // logit parked until the normaliser is known
-                    const float mn = fmaxf(m_run, t);
-                    const float sc = rescale(m_run, mn);
-                    const float w = expf(t - mn);
-                    s_run = s_run * sc + w;
-                    m_run = mn;
-#pragma unroll
-                    for (int j = 0; j < CPL; ++j)
-#pragma unroll
-                        for (int e = 0; e < EPC; ++e) dz[j][e] = fmaf(w, wf[j][e], dz[j][e] * sc);
-                    if (isp[u]) {
-                        loss_acc += t; ++npos;
-#pragma unroll
-                        for (int j = 0; j < CPL; ++j)
-#pragma unroll
-                            for (int e = 0; e < EPC; ++e) pz[j][e] += wf[j][e];
-                    }
+                        for (int e = 0; e < EPC; ++e) pz[j][e] += wf[j][e];
                 }
             }
+            float park = g;         // soft-max: the logit is parked until the normaliser is known
+            if (KIND == XC_LOSS_SOFTMAX) park = __shfl(my_t, src, kWave);
             if (gl == 0 && c < n) {
                 keys[p_base + c] = ok[u] ? static_cast<uint32_t>(id[u]) : static_cast<uint32_t>(L);
                 vals[p_base + c] = static_cast<uint32_t>(p_base + c);
-                gco[p_base + c] = g;
+                gco[p_base + c] = park;
             }
         }
+    }
+    // per-lane partial sums of the group (one lane per row adds) -> every lane of the group
+    for (int off = G >> 1; off > 0; off >>= 1) loss_acc += __shfl_xor(loss_acc, off, kWave);
+    if (KIND == XC_LOSS_SOFTMAX) {
+        for (int off = G >> 1; off > 0; off >>= 1) npos += __shfl_xor(npos, off, kWave);
     }
 
     // ---- combine the groups of the workgroup -------------------------------
     float lse = 0.0f, inv_sum = 0.0f, inv_npos = 0.0f;
     int npos_all = 0;
     if (KIND == XC_LOSS_BCE) {
-        if (gl == 0) part[grp] = loss_acc;
+        if (gl == 0) part[tid / G] = loss_acc;
         __syncthreads();
         if (tid == 0) {
             float t = 0.0f;
-            for (int g2 = 0; g2 < NG; ++g2) t += part[g2];
-            loss_q[i] = t;
+            for (int g2 = 0; g2 < kStepThreads / G; ++g2) t += part[g2];
+            loss_q[sq * B + i] = t;
         }
     } else {
         if (gl == 0) { part[grp] = m_run; part2[grp] = s_run; part3[grp] = loss_acc; part4[grp] = static_cast<float>(npos); }
@@ -245,7 +377,7 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
         float v = 0.0f;
 #pragma unroll
         for (int w = 0; w < kStepThreads / kWave; ++w) v += red[w][c];
-        dZ[i * d + c] = v;
+        dZ[(sq * B + i) * d + c] = v;
     }
 
     if (KIND == XC_LOSS_SOFTMAX) {
@@ -262,72 +394,74 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
 }
 
 // ---------------------------------------------------------------------------
-// loss = (1/B) sum_i loss_q[i], summed in a fixed order by one workgroup
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256)
-void loss_reduce_kernel(const float* __restrict__ loss_q, int64_t B, float inv_B, float* __restrict__ loss) {
-    __shared__ float sh[256];
-    float t = 0.0f;
-    for (int64_t i = threadIdx.x; i < B; i += 256) t += loss_q[i];
-    sh[threadIdx.x] = t;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) loss[0] = sh[0] * inv_B;
-}
-
-// ---------------------------------------------------------------------------
-// stable LSD radix sort of (key, value) pairs, 8 bits per pass.
+// stable LSD radix sort of (key, value) pairs, `rb` bits per pass (rb <= 11).
 // Block b owns the contiguous chunk [b*chunk, (b+1)*chunk) of the input.
+//   radix_count    per-block digit histogram -> counts[digit][block]
+//   radix_prefix   one wave per digit: exclusive prefix over the blocks, digit total
+//   radix_scatter  digit bases by a scan of the totals inside every block, then the
+//                  block walks its chunk tile by tile with running digit offsets
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256)
-void radix_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t chunk, int shift,
-                        int nb, int* __restrict__ counts /* [kRadix][nb] */) {
-    __shared__ int hist[kRadix];
-    hist[threadIdx.x] = 0;
+void radix_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t chunk, int shift, int rb,
+                        int nb, int* __restrict__ counts /* [radix][nb] */) {
+    __shared__ int hist[kMaxRadix];
+    const int radix = 1 << rb;
+    for (int d = threadIdx.x; d < radix; d += 256) hist[d] = 0;
     __syncthreads();
     const int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
     p1 = p1 < P ? p1 : P;
     for (int64_t p = p0 + threadIdx.x; p < p1; p += 256)
-        atomicAdd(&hist[(keys[p] >> shift) & (kRadix - 1)], 1);
+        atomicAdd(&hist[(keys[p] >> shift) & (radix - 1)], 1);
     __syncthreads();
-    counts[threadIdx.x * nb + blockIdx.x] = hist[threadIdx.x];
+    for (int d = threadIdx.x; d < radix; d += 256) counts[d * nb + blockIdx.x] = hist[d];
 }
 
-// exclusive scan of `n` ints in place, one workgroup of 1024 threads
-__global__ __launch_bounds__(1024)
-void scan_kernel(int* __restrict__ data, int n) {
-    __shared__ int wsum[16];
-    const int tid = threadIdx.x;
-    const int per = (n + 1023) / 1024;
-    const int b = tid * per;
-    int e = b + per;
-    e = e < n ? e : n;
-    int s = 0;
-    for (int x = b; x < e; ++x) s += data[x];
-    const int incl = wave_incl_scan(s);
-    if ((tid & 63) == 63) wsum[tid >> 6] = incl;
-    __syncthreads();
-    int off = 0;
-    for (int w = 0; w < (tid >> 6); ++w) off += wsum[w];
-    int run = off + incl - s;
-    for (int x = b; x < e; ++x) { const int v = data[x]; data[x] = run; run += v; }
+__global__ __launch_bounds__(kWave)
+void radix_prefix_kernel(int* __restrict__ counts /* [radix][nb], in place */, int nb,
+                         int* __restrict__ totals /* [radix] */) {
+    int* row = counts + static_cast<size_t>(blockIdx.x) * nb;
+    const int lane = threadIdx.x;
+    int run = 0;
+    for (int b0 = 0; b0 < nb; b0 += kWave) {
+        const int b = b0 + lane;
+        const int v = b < nb ? row[b] : 0;
+        const int incl = wave_incl_scan(v);
+        if (b < nb) row[b] = run + incl - v;
+        run += __shfl(incl, kWave - 1, kWave);
+    }
+    if (lane == 0) totals[blockIdx.x] = run;
 }
 
 __global__ __launch_bounds__(kSortTile)
 void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
                           uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, int64_t P,
-                          int64_t chunk, int shift, int nb, const int* __restrict__ offsets) {
-    __shared__ int offs[kRadix];
-    __shared__ int whist[kSortTile / kWave][kRadix];
+                          int64_t chunk, int shift, int rb, int nb, const int* __restrict__ prefix,
+                          const int* __restrict__ totals) {
+    __shared__ int offs[kMaxRadix];
+    __shared__ int whist[kSortTile / kWave][kMaxRadix];
+    __shared__ int wsum[kSortTile / kWave];
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
-    offs[tid] = offsets[tid * nb + blockIdx.x];
+    const int radix = 1 << rb;
+    const int per = (radix + kSortTile - 1) / kSortTile;     // digits per thread, contiguous
+    // digit bases: exclusive scan of the totals
+    {
+        int local = 0;
+        for (int j = 0; j < per; ++j) { const int d = tid * per + j; if (d < radix) local += totals[d]; }
+        const int incl = wave_incl_scan(local);
+        if ((tid & 63) == 63) wsum[wave] = incl;
+        __syncthreads();
+        int run = incl - local;
+        for (int w = 0; w < wave; ++w) run += wsum[w];
+        for (int j = 0; j < per; ++j) {
+            const int d = tid * per + j;
+            if (d < radix) { offs[d] = run + prefix[d * nb + blockIdx.x]; run += totals[d]; }
+        }
+    }
+    for (int d = tid; d < radix; d += kSortTile)
 #pragma unroll
-    for (int w = 0; w < kSortTile / kWave; ++w) whist[w][tid] = 0;
+        for (int w = 0; w < kSortTile / kWave; ++w) whist[w][d] = 0;
     __syncthreads();
     const int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
@@ -337,11 +471,10 @@ void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* 
         const bool valid = p < p1;
         uint32_t key = 0, val = 0;
         if (valid) { key = keys_in[p]; val = vals_in[p]; }
-        const int digit = (key >> shift) & (kRadix - 1);
+        const int digit = (key >> shift) & (radix - 1);
         // lanes of this wave holding the same digit
         uint64_t same = __ballot(valid);
-#pragma unroll
-        for (int b = 0; b < kRadixBits; ++b) {
+        for (int b = 0; b < rb; ++b) {
             const bool bit = (digit >> b) & 1;
             const uint64_t bal = __ballot(bit);
             same &= bit ? bal : ~bal;
@@ -356,10 +489,19 @@ void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* 
             vals_out[before + rank] = val;
         }
         __syncthreads();
-        int add = 0;
+        // only digits present in this tile need their running offset advanced
+        if (valid && rank == 0) {
+            int add = 0;
 #pragma unroll
-        for (int w = 0; w < kSortTile / kWave; ++w) { add += whist[w][tid]; whist[w][tid] = 0; }
-        offs[tid] += add;
+            for (int w = 0; w < kSortTile / kWave; ++w) add += whist[w][digit];
+            // one lane per (wave, digit); the wave holding the lowest index among the waves
+            // that saw the digit applies the update
+            bool first = true;
+            for (int w = 0; w < wave; ++w) first = first && whist[w][digit] == 0;
+            if (first) offs[digit] += add;
+        }
+        __syncthreads();
+        if (valid && rank == 0) whist[wave][digit] = 0;
         __syncthreads();
     }
 }
@@ -396,8 +538,10 @@ void heads_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
 __global__ __launch_bounds__(256)
 void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t chunk, uint32_t Lkey,
                         int nb, const int* __restrict__ head_cnt, const int* __restrict__ valid_cnt,
-                        int32_t* __restrict__ touched, int32_t* __restrict__ seg_start,
-                        int32_t* __restrict__ n_touched) {
+                        const uint32_t* __restrict__ vals, int32_t* __restrict__ touched,
+                        int32_t* __restrict__ seg_start, uint32_t* __restrict__ seg_idx0,
+                        int32_t* __restrict__ n_touched, const float* __restrict__ loss_q, int64_t B,
+                        float inv_B, float* __restrict__ loss, int SQ) {
     __shared__ int sh[256];
     __shared__ int wcnt[4];
     __shared__ int running;
@@ -424,6 +568,17 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
             __syncthreads();
         }
         if (tid == 0) { n_touched[0] = sh2[0][0]; seg_start[sh2[0][0]] = sh2[1][0]; }
+        // loss = (1/B) sum_i loss_q[i], summed in a fixed order
+        __shared__ float shf[256];
+        float t2 = 0.0f;
+        for (int64_t i = tid; i < B * SQ; i += 256) t2 += loss_q[i];
+        shf[tid] = t2;
+        __syncthreads();
+        for (int s = 128; s > 0; s >>= 1) {
+            if (tid < s) shf[tid] += shf[tid + s];
+            __syncthreads();
+        }
+        if (tid == 0) loss[0] = shf[0] * inv_B;
     }
     const int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
@@ -440,6 +595,7 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
             const int s = before + __popcll(bal & lanemask_lt());
             touched[s] = static_cast<int32_t>(keys[p]);
             seg_start[s] = static_cast<int32_t>(p);
+            seg_idx0[s] = vals[p];               // first pair of the segment, saves the update a hop
         }
         __syncthreads();
         if (tid == 0) running += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
@@ -453,66 +609,114 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
 // ---------------------------------------------------------------------------
 template <typename T, int CPL>
 __global__ __launch_bounds__(kStepThreads)
-void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, int n, int G,
+void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n_magic, int n_shift, int G,
                    const uint32_t* __restrict__ vals, const float* __restrict__ gco,
                    const int32_t* __restrict__ touched, const int32_t* __restrict__ seg_start,
-                   const int32_t* __restrict__ n_touched, float lr, T* __restrict__ rows_out) {
+                   const uint32_t* __restrict__ seg_idx0, const int32_t* __restrict__ n_touched, float lr,
+                   T* __restrict__ rows_out,
+                   const float* __restrict__ dz_part, int SQ, int64_t BD, float* __restrict__ dZ) {
     constexpr int EPC = Elem<T>::kPerChunk;
-    constexpr int U = 4;
+    constexpr int U = 2;
     const int tid = threadIdx.x;
+    // dZ = sum of the partials written by the workgroups that shared a query, in split order
+    // (independent of the row updates below; done here because this grid is large)
+    if (SQ > 1) {
+        for (int64_t e = static_cast<int64_t>(blockIdx.x) * kStepThreads + tid; e < BD;
+             e += static_cast<int64_t>(gridDim.x) * kStepThreads) {
+            float v = dz_part[e];
+            for (int q = 1; q < SQ; ++q) v += dz_part[q * BD + e];
+            dZ[e] = v;
+        }
+    }
     const int gl = tid & (G - 1);
     const int NG = kStepThreads / G;
-    const int64_t s = static_cast<int64_t>(blockIdx.x) * NG + tid / G;
-    if (s >= n_touched[0]) return;
     const int nchunks = d / EPC;
     const int64_t row_bytes = static_cast<int64_t>(d) * sizeof(T);
     const unsigned char* Zb = reinterpret_cast<const unsigned char*>(Z);
+    const int64_t n_seg = n_touched[0];
+    // a group walks several segments so that waves live long enough to keep the chip full
+    for (int64_t s = static_cast<int64_t>(blockIdx.x) * NG + tid / G; s < n_seg;
+         s += static_cast<int64_t>(gridDim.x) * NG) {
+    // hop 1: everything that identifies the segment
     const int p0 = seg_start[s], p1 = seg_start[s + 1];
     const int64_t label = touched[s];
+    const uint32_t idx0 = seg_idx0[s];
 
-    float acc[CPL][EPC];
-#pragma unroll
-    for (int j = 0; j < CPL; ++j)
-#pragma unroll
-        for (int e = 0; e < EPC; ++e) acc[j][e] = 0.0f;
+    // pair index -> query row: exact division by n through a multiply-high (n_magic, n_shift
+    // from the host; valid for every index below 2^31)
+    auto query_of = [&](uint32_t idx) -> int64_t {
+        if (n_shift < 0) return static_cast<int64_t>(idx);           // n == 1
+        const uint32_t t = __umulhi(idx, n_magic);
+        return static_cast<int64_t>((t + ((idx - t) >> 1)) >> n_shift);
+    };
 
-    for (int p = p0; p < p1; p += U) {
-        float g[U];
-        uint4 rz[U][CPL];
+    // hop 2: the row of W, the coefficient and the query row of the first pair, together
+    unsigned char* wrow = reinterpret_cast<unsigned char*>(W) + label * row_bytes;
+    uint4 wv[CPL], z0[CPL];
+    const float g0 = gco[idx0];
+    {
+        const int64_t qi = query_of(idx0);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            g[u] = 0.0f;
-            const bool on = p + u < p1;
-            uint32_t idx = 0;
-            if (on) { idx = vals[p + u]; g[u] = gco[idx]; }
-            const int64_t qi = idx / static_cast<uint32_t>(n);
-#pragma unroll
-            for (int j = 0; j < CPL; ++j) {
-                const int ch = gl + j * G;
-                rz[u][j] = make_uint4(0, 0, 0, 0);
-                if (on && ch < nchunks) rz[u][j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-#pragma unroll
-            for (int j = 0; j < CPL; ++j) {
-                float zf[EPC];
-                Elem<T>::unpack(rz[u][j], zf);
-#pragma unroll
-                for (int e = 0; e < EPC; ++e) acc[j][e] = fmaf(g[u], zf[e], acc[j][e]);
+        for (int j = 0; j < CPL; ++j) {
+            const int ch = gl + j * G;
+            wv[j] = make_uint4(0, 0, 0, 0);
+            z0[j] = make_uint4(0, 0, 0, 0);
+            if (ch < nchunks) {
+                wv[j] = *reinterpret_cast<const uint4*>(wrow + ch * 16);
+                z0[j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
             }
         }
     }
-    unsigned char* wrow = reinterpret_cast<unsigned char*>(W) + label * row_bytes;
+
+    float acc[CPL][EPC];
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) {
+        float zf[EPC];
+        Elem<T>::unpack(z0[j], zf);
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[j][e] = g0 * zf[e];
+    }
+
+    // further pairs of the same label, in sorted (= original) order
+    for (int p = p0 + 1; p < p1; p += U) {
+        float g[U];
+        uint32_t idx[U];
+        uint4 rz[U][CPL];
+#pragma unroll
+        for (int u = 0; u < U; ++u) idx[u] = p + u < p1 ? vals[p + u] : 0u;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (p + u < p1) {
+                g[u] = gco[idx[u]];
+                const int64_t qi = query_of(idx[u]);
+#pragma unroll
+                for (int j = 0; j < CPL; ++j) {
+                    const int ch = gl + j * G;
+                    rz[u][j] = make_uint4(0, 0, 0, 0);
+                    if (ch < nchunks) rz[u][j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (p + u < p1) {
+#pragma unroll
+                for (int j = 0; j < CPL; ++j) {
+                    float zf[EPC];
+                    Elem<T>::unpack(rz[u][j], zf);
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) acc[j][e] = fmaf(g[u], zf[e], acc[j][e]);
+                }
+            }
+        }
+    }
     unsigned char* orow = rows_out ? reinterpret_cast<unsigned char*>(rows_out) + s * row_bytes : nullptr;
 #pragma unroll
     for (int j = 0; j < CPL; ++j) {
         const int ch = gl + j * G;
         if (ch < nchunks) {
             float wf[EPC];
-            const uint4 v = *reinterpret_cast<const uint4*>(wrow + ch * 16);
-            Elem<T>::unpack(v, wf);
+            Elem<T>::unpack(wv[j], wf);
 #pragma unroll
             for (int e = 0; e < EPC; ++e) wf[e] = fmaf(-lr, acc[j][e], wf[e]);
             const uint4 o = Elem<T>::pack(wf);
@@ -520,6 +724,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, int n, int
             if (orow) *reinterpret_cast<uint4*>(orow + ch * 16) = o;
         }
     }
+    }   // segments of this group
 }
 
 // ---------------------------------------------------------------------------
@@ -527,15 +732,16 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, int n, int
 // ---------------------------------------------------------------------------
 struct StepPlan {
     int64_t P;
-    int n, G, cpl, nb, passes, key_bits;
+    int n, G, cpl, nb, passes, rb, key_bits, sq, n_shift;
+    uint32_t n_magic;
     int64_t chunk;
-    size_t off_keys0, off_keys1, off_vals0, off_vals1, off_g, off_lossq, off_counts, off_headcnt,
-        off_validcnt, off_segstart, total;
+    size_t off_keys0, off_keys1, off_vals0, off_vals1, off_g, off_lossq, off_dzpart, off_counts, off_totals, off_headcnt,
+        off_validcnt, off_segstart, off_segidx0, total;
 };
 
 static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t, StepPlan* p) {
     if (t != XC_F32 && t != XC_BF16) return XC_EINVAL;
-    if (B < 1 || d < 1 || k_p < 0 || n_neg < 0) return XC_ESHAPE;
+    if (B < 1 || d < 1 || k_p < 0 || k_p > XC_MAX_KP || n_neg < 0) return XC_ESHAPE;
     const int64_t n = static_cast<int64_t>(k_p) + n_neg;
     if (n < 1 || n > XC_MAX_CANDIDATES) return XC_ESHAPE;
     const int64_t row_bytes = static_cast<int64_t>(d) * (t == XC_F32 ? 4 : 2);
@@ -543,6 +749,13 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     if (B * n >= 0x7fffffffLL) return XC_ESHAPE;
     p->P = B * n;
     p->n = static_cast<int>(n);
+    {   // floor(x / n) = (t + ((x - t) >> 1)) >> n_shift with t = mulhi(x, n_magic), for all 32-bit x
+        int sh = 0;
+        while ((static_cast<int64_t>(1) << sh) < n) ++sh;
+        p->n_magic = static_cast<uint32_t>(((static_cast<uint64_t>(1) << 32) * ((static_cast<uint64_t>(1) << sh) - static_cast<uint64_t>(n))) / static_cast<uint64_t>(n) + 1);
+        p->n_shift = sh > 0 ? sh - 1 : 0;
+        if (n == 1) { p->n_magic = 0; p->n_shift = -1; }      // identity
+    }
     const int nchunks = static_cast<int>(row_bytes / 16);
     int G = 16;
     while (G < 64 && G * 4 < nchunks) G <<= 1;     // at most 4 chunks per lane
@@ -550,7 +763,7 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     p->G = G;
     p->cpl = (nchunks + G - 1) / G;
     if (p->cpl > 4) return XC_ESHAPE;
-    int nb = static_cast<int>((p->P + 2047) / 2048);
+    int nb = static_cast<int>((p->P + 511) / 512);        // two 256-key tiles per block at least
     if (nb > kSortMaxBlocks) nb = kSortMaxBlocks;
     if (nb < 1) nb = 1;
     int64_t chunk = (p->P + nb - 1) / nb;
@@ -561,18 +774,24 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     int bits = 1;
     if (L >= 0) { while ((static_cast<int64_t>(1) << bits) <= L && bits < 32) ++bits; }
     p->key_bits = bits;                                // keys take values 0..L
-    p->passes = (bits + kRadixBits - 1) / kRadixBits;
+    p->passes = (bits + kMaxRadixBits - 1) / kMaxRadixBits;
+    p->rb = (bits + p->passes - 1) / p->passes;          // digit width, <= 11 bits
     size_t off = 0;
     auto take = [&off](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
     const size_t P = static_cast<size_t>(p->P);
     p->off_keys0 = take(P * 4); p->off_keys1 = take(P * 4);
     p->off_vals0 = take(P * 4); p->off_vals1 = take(P * 4);
     p->off_g = take(P * 4);
-    p->off_lossq = take(static_cast<size_t>(B) * 4);
-    p->off_counts = take(static_cast<size_t>(kRadix) * nb * 4);
+    // few queries: several workgroups share a query so that the chip is filled
+    p->sq = B >= 1536 ? 1 : (B >= 768 ? 2 : 4);
+    p->off_lossq = take(static_cast<size_t>(B) * p->sq * 4);
+    p->off_dzpart = take(p->sq > 1 ? static_cast<size_t>(B) * p->sq * d * 4 : 0);
+    p->off_counts = take(static_cast<size_t>(kMaxRadix) * nb * 4);
+    p->off_totals = take(static_cast<size_t>(kMaxRadix) * 4);
     p->off_headcnt = take(static_cast<size_t>(nb) * 4);
     p->off_validcnt = take(static_cast<size_t>(nb) * 4);
     p->off_segstart = take((P + 1) * 4);
+    p->off_segidx0 = take(P * 4);
     p->total = off;
     return XC_OK;
 }
@@ -581,13 +800,21 @@ template <typename T, int KIND>
 static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, const void* W, int64_t B,
                           int64_t L, int d, const int32_t* pos, int k_p, const int32_t* neg,
                           const float* logq, int n_neg, uint32_t* keys, uint32_t* vals, float* gco,
-                          float* loss_q, float* dZ) {
+                          float* loss_q, float* dZ, int SQ) {
     const float inv_B = 1.0f / static_cast<float>(B);
-    const dim3 grid(static_cast<unsigned>(B));
-#define XC_GATHER(CPL)                                                                              \
-    XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND><<<grid, kStepThreads, 0, st>>>(            \
-        static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg, pl.G, \
-        inv_B, keys, vals, gco, loss_q, dZ)))
+    const dim3 grid(static_cast<unsigned>(B * SQ));
+#define XC_GATHER(CPL)                                                                                 \
+    do {                                                                                               \
+        if (B * SQ <= 1024) {   /* few workgroups: more rows in flight per group */                   \
+            XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, 8><<<grid, kStepThreads, 0, st>>>(    \
+                static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg,  \
+                pl.G, SQ, B, inv_B, keys, vals, gco, loss_q, dZ)));                                    \
+        } else {                                                                                       \
+            XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, 4><<<grid, kStepThreads, 0, st>>>(    \
+                static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg,  \
+                pl.G, SQ, B, inv_B, keys, vals, gco, loss_q, dZ)));                                    \
+        }                                                                                              \
+    } while (0)
     switch (pl.cpl) {
         case 1: XC_GATHER(1); break;
         case 2: XC_GATHER(2); break;
@@ -600,13 +827,19 @@ static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, con
 template <typename T>
 static void launch_update(const StepPlan& pl, hipStream_t st, const void* Z, void* W, int d,
                           const uint32_t* vals, const float* gco, const int32_t* touched,
-                          const int32_t* seg_start, const int32_t* n_touched, float lr, void* rows_out) {
+                          const int32_t* seg_start, const uint32_t* seg_idx0, const int32_t* n_touched,
+                          float lr, void* rows_out,
+                          const float* dz_part, int SQ, int64_t BD, float* dZ) {
     const int NG = kStepThreads / pl.G;
-    const dim3 grid(static_cast<unsigned>((pl.P + NG - 1) / NG));
+    // a pair per group would need P/NG workgroups; with several segments per group the grid is
+    // bounded by what the chip holds at once
+    int64_t nwg = (pl.P + NG - 1) / NG;
+    if (nwg > kUpdateMaxGrid) nwg = kUpdateMaxGrid;
+    const dim3 grid(static_cast<unsigned>(nwg));
 #define XC_UPDATE(CPL)                                                                            \
     XC_LAUNCH(K_UPDATE, st, (update_kernel<T, CPL><<<grid, kStepThreads, 0, st>>>(                \
-        static_cast<const T*>(Z), static_cast<T*>(W), d, pl.n, pl.G, vals, gco, touched, seg_start, \
-        n_touched, lr, static_cast<T*>(rows_out))))
+        static_cast<const T*>(Z), static_cast<T*>(W), d, pl.n_magic, pl.n_shift, pl.G, vals, gco, touched, seg_start, \
+        seg_idx0, n_touched, lr, static_cast<T*>(rows_out), dz_part, SQ, BD, dZ)))
     switch (pl.cpl) {
         case 1: XC_UPDATE(1); break;
         case 2: XC_UPDATE(2); break;
@@ -656,43 +889,47 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
     float* gco = reinterpret_cast<float*>(w8 + pl.off_g);
     float* loss_q = reinterpret_cast<float*>(w8 + pl.off_lossq);
     int* counts = reinterpret_cast<int*>(w8 + pl.off_counts);
+    int* totals = reinterpret_cast<int*>(w8 + pl.off_totals);
     int* head_cnt = reinterpret_cast<int*>(w8 + pl.off_headcnt);
     int* valid_cnt = reinterpret_cast<int*>(w8 + pl.off_validcnt);
     int32_t* seg_start = reinterpret_cast<int32_t*>(w8 + pl.off_segstart);
+    uint32_t* seg_idx0 = reinterpret_cast<uint32_t*>(w8 + pl.off_segidx0);
 
     // S3 + S4
+    const int SQ = kind == XC_LOSS_BCE ? pl.sq : 1;      // the soft-max normaliser needs the whole query
+    float* dz_target = SQ > 1 ? reinterpret_cast<float*>(w8 + pl.off_dzpart) : dZ;
     if (t == XC_BF16) {
         if (kind == XC_LOSS_BCE)
-            launch_gather<bf16_t, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dZ);
+            launch_gather<bf16_t, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dz_target, SQ);
         else
-            launch_gather<bf16_t, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dZ);
+            launch_gather<bf16_t, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dz_target, SQ);
     } else {
         if (kind == XC_LOSS_BCE)
-            launch_gather<float, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dZ);
+            launch_gather<float, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dz_target, SQ);
         else
-            launch_gather<float, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dZ);
+            launch_gather<float, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dz_target, SQ);
     }
-    XC_HIP_CHECK(hipGetLastError());
-    XC_LAUNCH(K_LOSS_REDUCE, st, (loss_reduce_kernel<<<1, 256, 0, st>>>(loss_q, B, 1.0f / static_cast<float>(B), loss)));
     XC_HIP_CHECK(hipGetLastError());
 
     // S5: sort pairs by label
     uint32_t *kin = keys0, *kout = keys1, *vin = vals0, *vout = vals1;
     for (int pass = 0; pass < pl.passes; ++pass) {
-        const int shift = pass * kRadixBits;
-        XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.nb, counts)));
-        XC_LAUNCH(K_RADIX_SCAN, st, (scan_kernel<<<1, 1024, 0, st>>>(counts, kRadix * pl.nb)));
-        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, 0, st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.nb, counts)));
+        const int shift = pass * pl.rb;
+        const int radix = 1 << pl.rb;
+        XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts)));
+        XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
+        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, 0, st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals)));
         XC_HIP_CHECK(hipGetLastError());
         uint32_t* tk = kin; kin = kout; kout = tk;
         uint32_t* tv = vin; vin = vout; vout = tv;
     }
     XC_LAUNCH(K_HEADS_COUNT, st, (heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt)));
     XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
-                                                                            valid_cnt, touched, seg_start, n_touched)));
+                                                                            valid_cnt, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
+                                                                            1.0f / static_cast<float>(B), loss, SQ)));
     XC_HIP_CHECK(hipGetLastError());
-    if (t == XC_BF16) launch_update<bf16_t>(pl, st, Z, W, d, vin, gco, touched, seg_start, n_touched, lr, W_rows_out);
-    else launch_update<float>(pl, st, Z, W, d, vin, gco, touched, seg_start, n_touched, lr, W_rows_out);
+    if (t == XC_BF16) launch_update<bf16_t>(pl, st, Z, W, d, vin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
+    else launch_update<float>(pl, st, Z, W, d, vin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
     XC_HIP_CHECK(hipGetLastError());
     return XC_OK;
 }
