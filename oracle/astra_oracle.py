@@ -142,7 +142,7 @@ def complement_select(hs_sorted, r: int) -> int:
     return r + c
 
 
-def sample_negatives(shortlist, B: int, k_h: int, k_r: int, L: int, seed: int):
+def sample_negatives(shortlist, B: int, k_h: int, k_r: int, L: int, seed: int, rows=None):
     """Negatives and log-proposal for one mini-batch.
 
     shortlist: int [B, k_h] (row i = stale hard negatives of query i) or None
@@ -155,11 +155,13 @@ def sample_negatives(shortlist, B: int, k_h: int, k_r: int, L: int, seed: int):
     logq = log(k_r / (L - u_i)), the log of the expected number of copies of a
     label among the draws, so that exp(-logq) = 1/(p k_r) of Eq. 2.
     Warm-up mode: all k_h+k_r slots uniform on [L], logq = log((k_h+k_r)/L).
+    `rows` (optional) restricts the work to those query indices of the batch; the
+    other rows of the outputs are left at -1 / 0 (used to spot-check large batches).
     """
     n = k_h + k_r
-    neg = np.empty((B, n), dtype=np.int32)
-    logq = np.empty((B, n), dtype=np.float32)
-    for i in range(B):
+    neg = np.full((B, n), -1, dtype=np.int32)
+    logq = np.zeros((B, n), dtype=np.float32)
+    for i in (range(B) if rows is None else rows):
         if shortlist is None:
             hs = []
             n_draw, first = n, 0

@@ -65,6 +65,18 @@ def gaussian_rows(seed: int, tag: int, row0: int, nrows: int, d: int,
     return (s * c).to(dtype).reshape(nrows, d)
 
 
+def gaussian_rows_at(seed: int, tag: int, rows: torch.Tensor, d: int, dtype: torch.dtype) -> torch.Tensor:
+    """The rows with the given indices (int64 tensor, any device) of the same tensor."""
+    rows = rows.to(torch.int64)
+    e = (rows[:, None] * d + torch.arange(d, dtype=torch.int64, device=rows.device)[None, :]).reshape(-1)
+    h = _hash64(e * _GOLD + _tensor_seed(seed, tag))
+    s = (h & 0xFFFF) + (_lsr(h, 16) & 0xFFFF) + (_lsr(h, 32) & 0xFFFF) + _lsr(h, 48)
+    s = (s - 2 * 65535).to(torch.float32)
+    var = 4.0 * (65536.0 ** 2 - 1.0) / 12.0
+    c = torch.tensor(1.0 / math.sqrt(d * var), dtype=torch.float32, device=rows.device)
+    return (s * c).to(dtype).reshape(rows.numel(), d)
+
+
 def make_matrix(seed: int, tag: int, nrows: int, d: int, dtype: torch.dtype,
                 device="cpu", chunk_rows: int | None = None) -> torch.Tensor:
     """Whole [nrows, d] tensor, generated in chunks to bound temporaries."""

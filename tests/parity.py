@@ -56,12 +56,15 @@ def check_rows_close(got, want, tol, what):
     return err
 
 
-def check_bf16_rows(got, want, old, what, max_mismatch_frac=2e-3):
+def check_bf16_rows(got, want, old, what, max_mismatch_frac=2e-3, slack=None):
     """Stored bf16 rows: norm-wise 2e-3 (the stated bar), and element-wise at
     most one bf16 ulp apart, on a small fraction of elements only: an fp32 sum
     and an fp64 sum can straddle a rounding boundary.  Where the update nearly
     cancels the old value the ulp of the result is tiny, so the fp32 error of
-    the operands (2^-20 of the old element) is allowed on top."""
+    the operands (2^-18 of the larger of old and new element: sums in float32 and
+    hardware exp2/log2/rcp in the coefficients) is allowed on top.  `slack`
+    (per row, optional) adds the float32 error of a gradient sum whose terms cancel:
+    the caller passes about 2e-6 * lr * sum|g| * max|z| of the row."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     old = np.asarray(old, dtype=np.float64)
@@ -74,7 +77,9 @@ def check_bf16_rows(got, want, old, what, max_mismatch_frac=2e-3):
     _, e = np.frexp(np.maximum(np.abs(want), np.abs(got)))
     ulp = np.ldexp(1.0, np.maximum(e, -125) - 8)
     diff = np.abs(got - want)
-    allowed = ulp * 1.0000001 + 2.0 ** -20 * np.maximum(np.abs(old), np.abs(want))
+    allowed = ulp * 1.0000001 + 2.0 ** -18 * np.maximum(np.abs(old), np.abs(want))
+    if slack is not None:
+        allowed = allowed + np.asarray(slack, dtype=np.float64).reshape(-1, 1)
     assert (diff <= allowed).all(), (what, (diff / allowed).max())
     frac = (diff > 0).mean()
     assert frac <= max_mismatch_frac, (what, frac)
