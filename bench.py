@@ -38,6 +38,9 @@ def parse_args():
     ap.add_argument("--pool", type=int, default=0, help="override the mined query pool size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also launch the library's plain copy kernel over this many MiB (three times), "
+                         "for scaling hardware traffic counters in rocprofv3 --pmc runs")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch from rocprofv3 --pmc runs, if present")
     return ap.parse_args()
@@ -158,6 +161,14 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     value = wl.B * args.steps / elapsed
 
+    if args.copy_probe_mib:
+        a = torch.randint(0, 255, (args.copy_probe_mib << 20,), dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            binding.copy_probe(b, a)
+        torch.cuda.synchronize()
+        del a, b
+
     # ---- second pass: the same number of steps with per-kernel HIP events --------------
     roofline, kernels, mines = None, {}, 0
     if not args.no_profile_pass:
@@ -205,7 +216,8 @@ def main():
                 traffic = {}
         for name, m in models.items():
             m["frac"] = m["achieved"] / m["peak"]
-            m["traffic"] = traffic.get(name)
+            t = traffic.get(name)
+            m["traffic"] = t["bytes"] if t else None       # HBM bytes per launch (read + written)
             m["kernel"] = name
             m["avg_us"] = kernels[name]["avg_us"]
         if models:

@@ -138,6 +138,13 @@ int xc_profile_collect(void);
 int xc_profile_get(int i, const char** name, double* total_ms, int64_t* launches);
 int xc_profile_reset(void);
 
+/* Measurement aid: a plain device-to-device copy kernel (reads `bytes`, writes `bytes`;
+ * both pointers device memory, 16-byte aligned, `bytes` a multiple of 16, buffers must not
+ * overlap).  The benchmark launches it beside the library's kernels in hardware-counter runs
+ * so that the traffic counters can be scaled by a kernel of known size.  Asynchronous on
+ * `stream`.  XC_EINVAL on null or misaligned arguments. */
+int xc_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

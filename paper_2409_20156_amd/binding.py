@@ -34,6 +34,7 @@ _SIGNATURES = {
     "xc_profile_get": (_i32, [_i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
                               ctypes.POINTER(ctypes.c_int64)]),
     "xc_profile_reset": (_i32, []),
+    "xc_copy_probe": (_i32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "xc_step": (_i32, [_ptr, _ptr, _i64, _i64, _i32, _ptr, _i32, _ptr, _ptr, _i32, _f32, _i32, _i32,
                        _ptr, _ptr, _ptr, _ptr, _ptr, _ptr, ctypes.c_size_t, _ptr]),
 }
@@ -215,3 +216,11 @@ def profile_collect() -> dict:
         _check(lib.xc_profile_get(i, ctypes.byref(name), ctypes.byref(ms), ctypes.byref(cnt)), "xc_profile_get")
         out[name.value.decode()] = (ms.value, cnt.value)
     return out
+
+
+def copy_probe(dst, src) -> None:
+    """Launch the plain copy kernel over two equal-sized uint8 device tensors (counter calibration)."""
+    if dst.numel() != src.numel():
+        raise ValueError("copy_probe: sizes differ")
+    _check(load_library().xc_copy_probe(_dev(dst, torch.uint8, "dst"), _dev(src, torch.uint8, "src"),
+                                        src.numel(), _stream()), "xc_copy_probe")

@@ -43,7 +43,28 @@ void profile_mark(int kernel_id, hipStream_t st, bool begin) {
     }
 }
 
+// Plain copy, 16 bytes per lane per trip: a kernel whose HBM traffic is known (n16*16 bytes
+// read and as many written), used to calibrate hardware traffic counters.
+__global__ __launch_bounds__(256) void copy_probe_kernel(uint4* __restrict__ dst,
+                                                         const uint4* __restrict__ src, int64_t n16) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride)
+        dst[i] = src[i];
+}
+
 }  // namespace xc
+
+extern "C" int xc_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || (bytes & 15) || ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15))
+        return XC_EINVAL;
+    if (bytes == 0) return XC_OK;
+    const int64_t n16 = static_cast<int64_t>(bytes / 16);
+    const int grid = static_cast<int>(n16 / 256 < 8192 ? (n16 + 255) / 256 : 8192);
+    xc::copy_probe_kernel<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+    XC_HIP_CHECK(hipGetLastError());
+    return XC_OK;
+}
 
 extern "C" const char* xc_strerror(int status) {
     switch (status) {

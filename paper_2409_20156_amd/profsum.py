@@ -1,0 +1,104 @@
+"""Turn rocprofv3 CSV output into the short summaries kept with the benchmark.
+
+  python -m paper_2409_20156_amd.profsum stats  <kernel_stats.csv> <out.md> "<title>" "<command>"
+  python -m paper_2409_20156_amd.profsum pmc    <workload> <fetch counter csv> <write counter csv>
+                                                <copy MiB> <out.md> <traffic.json> "<commands>"
+
+`stats` lists the library's kernels from a `--kernel-trace --stats` run.  `pmc` averages
+FETCH_SIZE and WRITE_SIZE (KiB per dispatch) per library kernel, scales each by what the same
+counter read for the plain copy kernel of known size in the same run, and writes bytes per
+launch into the JSON file the benchmark reads.
+"""
+from __future__ import annotations
+
+import csv
+import json
+import os
+import sys
+from collections import defaultdict
+
+# kernel function name -> name used by the benchmark
+KERNELS = {"mine_tile_kernel": "mine_tile", "mine_select_kernel": "mine_select", "mine_init_kernel": "mine_init",
+           "sample_kernel": "sample", "gather_kernel": "gather", "radix_count_kernel": "radix_count",
+           "radix_prefix_kernel": "radix_scan", "radix_scatter_kernel": "radix_scatter",
+           "heads_count_kernel": "heads_count", "heads_write_kernel": "heads_write",
+           "update_kernel": "update", "copy_probe_kernel": "copy_probe"}
+
+
+def short_name(full: str):
+    if "xc::" not in full:
+        return None
+    fn = full.split("xc::")[1].split("(")[0].split("<")[0]
+    return KERNELS.get(fn, fn)
+
+
+def stats(src, out, title, cmd):
+    rows = list(csv.DictReader(open(src)))
+    agg = defaultdict(lambda: [0, 0, 1 << 62, 0, 0.0])
+    for r in rows:
+        n = short_name(r["Name"])
+        if n is None:
+            continue
+        a = agg[n]
+        a[0] += int(r["Calls"])
+        a[1] += int(r["TotalDurationNs"])
+        a[2] = min(a[2], int(r["MinNs"]))
+        a[3] = max(a[3], int(r["MaxNs"]))
+        a[4] += float(r["Percentage"])
+    with open(out, "w") as f:
+        f.write("# %s\n\nCommand (on the MI355X box, from the repository root):\n\n```\n%s\n```\n\n" % (title, cmd))
+        f.write("rocprofv3 kernel statistics of the library's kernels (template instances of one kernel "
+                "summed; torch's input-generator kernels omitted):\n\n")
+        f.write("| kernel | calls | total ms | avg us | min us | max us | % of all GPU time |\n|---|---|---|---|---|---|---|\n")
+        for n, a in sorted(agg.items(), key=lambda kv: -kv[1][1]):
+            f.write("| %s | %d | %.3f | %.2f | %.2f | %.2f | %.2f |\n"
+                    % (n, a[0], a[1] / 1e6, a[1] / a[0] / 1e3, a[2] / 1e3, a[3] / 1e3, a[4]))
+
+
+def _counter_means(path, counter):
+    tot, cnt = defaultdict(float), defaultdict(int)
+    for r in csv.DictReader(open(path)):
+        if r.get("Counter_Name") != counter:
+            continue
+        n = short_name(r["Kernel_Name"])
+        if n is None:
+            continue
+        tot[n] += float(r["Counter_Value"])
+        cnt[n] += 1
+    return {n: tot[n] / cnt[n] for n in tot}, dict(cnt)
+
+
+def pmc(workload, fetch_csv, write_csv, copy_mib, out, traffic_json, cmd):
+    fetch, nf = _counter_means(fetch_csv, "FETCH_SIZE")
+    write, _ = _counter_means(write_csv, "WRITE_SIZE")
+    copy_kib = float(copy_mib) * 1024.0
+    kf = copy_kib / fetch["copy_probe"]          # true KiB per counted KiB, reads
+    kw = copy_kib / write["copy_probe"]
+    result = {}
+    with open(out, "w") as f:
+        f.write("# HBM traffic per launch, workload %s\n\nCommands (on the MI355X box, from the repository root):\n\n```\n%s\n```\n\n"
+                % (workload, cmd))
+        f.write("The copy kernel moved %s MiB each way; the counters read %.1f KiB (FETCH_SIZE) and %.1f KiB "
+                "(WRITE_SIZE) for it, so the scale factors are %.4f and %.4f.\n\n"
+                % (copy_mib, fetch["copy_probe"], write["copy_probe"], kf, kw))
+        f.write("| kernel | dispatches | FETCH_SIZE KiB | WRITE_SIZE KiB | scaled read MB | scaled written MB |\n|---|---|---|---|---|---|\n")
+        for n in sorted(fetch, key=lambda n: -fetch[n]):
+            rd = fetch[n] * kf * 1024.0
+            wr = write.get(n, 0.0) * kw * 1024.0
+            f.write("| %s | %d | %.1f | %.1f | %.3f | %.3f |\n" % (n, nf[n], fetch[n], write.get(n, 0.0), rd / 1e6, wr / 1e6))
+            if n != "copy_probe":
+                result[n] = {"read_bytes": rd, "write_bytes": wr, "bytes": rd + wr}
+    data = {}
+    if os.path.exists(traffic_json):
+        data = json.load(open(traffic_json))
+    data[workload] = result
+    json.dump(data, open(traffic_json, "w"), indent=1, sort_keys=True)
+
+
+if __name__ == "__main__":
+    if len(sys.argv) >= 2 and sys.argv[1] == "stats":
+        stats(*sys.argv[2:6])
+    elif len(sys.argv) >= 2 and sys.argv[1] == "pmc":
+        pmc(*sys.argv[2:9])
+    else:
+        sys.exit(__doc__)
