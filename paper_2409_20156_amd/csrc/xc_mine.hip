@@ -8,14 +8,17 @@
 // k best labels overall are never below it and only about 8k scores per query
 // pass it.
 //   mine_tile_kernel    persistent tiled MFMA product W_tile x Z_tile^T (256
-//       labels x 256 queries per workgroup, 8 waves of 128 x 64).  Labels run
-//       along the MFMA M axis and queries along N, so one lane owns one query
-//       column and compares its accumulators with that query's tau; the score
-//       matrix never leaves registers.  Survivors go, as 64-bit (score,id)
-//       keys, to a 512-key list per query and are appended to the query's
-//       global candidate list when the workgroup finishes its label slice.  A
-//       list that could overflow is cut to its best k by one wave (radix
-//       select) and tau rises locally: only adversarial score orders get there.
+//       labels x 256 queries per workgroup, 8 waves of 128 x 64), K staged 64
+//       elements at a time through two LDS buffers that are filled by direct
+//       global->LDS loads one stage ahead.  Labels run along the MFMA M axis
+//       and queries along N, so one lane owns one query column and compares its
+//       accumulators with that query's tau; the score matrix never leaves
+//       registers.  Passing scores are parked in a per-wave stash in LDS (slot
+//       from a ballot, no atomic on the path), emptied 64 at a time into a
+//       512-key list per query, and appended to the query's global candidate
+//       list when the workgroup finishes its label slice.  A list that could
+//       overflow is cut to its best k by one wave (radix select) and tau rises
+//       locally: only adversarial score orders get there.
 //   mine_select_kernel  after each phase, one wave per query cuts the global
 //       candidate list to its best k and publishes the new tau; after the last
 //       phase it sorts the winners by (score descending, id ascending).
@@ -25,15 +28,18 @@ namespace xc {
 
 constexpr int kBM = 256;            // labels per tile   (MFMA M)
 constexpr int kBN = 256;            // queries per tile  (MFMA N)
-constexpr int kStageBytes = 128;    // bytes of a row staged in LDS per K step
-constexpr int kRowStride = kStageBytes + 16;   // padded LDS row pitch (conflict-free 16-byte reads)
+constexpr int kStageBytes = 128;    // bytes of a row staged in LDS per K step (= LDS row pitch; the
+                                    // 16-byte chunks of a row are stored swizzled, see lds_chunk_swizzle)
 constexpr int kCandCap = 512;       // keys per query candidate list
+constexpr int kStash = 1024;        // passing scores a wave parks in LDS before it empties them into the lists
 constexpr int kMineThreads = 512;   // 8 waves: 2 along labels x 4 along queries
 constexpr int kMineWaves = kMineThreads / kWave;
+static_assert(kMineWaves * kStash * 8 <= (kBM + kBN) * kStageBytes, "the stashes share one stage buffer");
 constexpr int kMineGrid = 256;      // persistent workgroups, one per compute unit
 constexpr int kXcds = 8;            // workgroup w runs on XCD w % 8
 constexpr int kCusPerXcd = kMineGrid / kXcds;
 constexpr int kPhaseGrowth = 8;     // labels of a phase / labels before it
+constexpr int kMaxSlices = 64;      // label slices of a phase at most (one lane per slice in the select)
 constexpr int kSelectRegs = 16;     // keys per lane held in registers by the phase select
 constexpr uint32_t kTauInit = 0x007fffffu;   // ordered image of -inf
 
@@ -42,12 +48,12 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // ---------------------------------------------------------------------------
 // Reduce a candidate list of n > k keys to its k smallest keys (best scores).
-// One wave; n <= 64*R keys, held in registers.  Radix select, most significant byte first, with a
+// One wave; n <= 64*R keys, fetched by load(index) and held in registers.  Radix select, most significant byte first, with a
 // 256-bin histogram in LDS; stops as soon as every key sharing the prefix is
 // needed.  Writes the survivors to buf[0..k), returns the score of the k-th.
 // ---------------------------------------------------------------------------
-template <int R>
-__device__ __noinline__ float wave_select_k(uint64_t* __restrict__ buf, int n, int k, int* hist) {
+template <int R, typename Load>
+__device__ __noinline__ float wave_select_k(uint64_t* __restrict__ buf, Load load, int n, int k, int* hist) {
     const int lane = lane_id();
     uint64_t key[R];
     bool valid[R];
@@ -55,7 +61,7 @@ __device__ __noinline__ float wave_select_k(uint64_t* __restrict__ buf, int n, i
     for (int r = 0; r < R; ++r) {
         const int idx = r * kWave + lane;
         valid[r] = idx < n;
-        key[r] = valid[r] ? buf[idx] : kKeySentinel;
+        key[r] = valid[r] ? load(idx) : kKeySentinel;
     }
     uint64_t prefix = 0, pmask = 0;
     int need = k;
@@ -156,27 +162,42 @@ struct MineArgs {
     uint64_t* glist;         // [nQT*kBN][glist_cap] per-query candidates across slices and phases
     int32_t* gcnt;           // [nQT*kBN] fill of glist
     const uint32_t* tau_g;   // [nQT*kBN] ordered image of the phase threshold
+    const unsigned char* zeros;   // 256 zero bytes (source of the chunks past the end of a row)
 };
 
-// One K stage of the W tile and the Z tile is 512 rows x 8 chunks of 16 bytes:
-// 8 chunks per thread (rows r, r+64, r+128, r+192 of W and of Z, r = tid/8, chunk
-// column tid%8).
-struct StageRegs { uint4 w[4], z[4]; };
+// ---------------------------------------------------------------------------
+// LDS staging.  One K stage is 512 rows (256 of W, then 256 of Z) x 128 bytes, row pitch 128.
+// Chunk c (16 bytes) of row r is stored at chunk position c ^ ((r >> 1) & 7): the 16 lanes
+// that read the same chunk of 16 consecutive rows for an MFMA operand then hit 16 different
+// 16-byte bank groups.  The stage is filled by direct global->LDS loads: lane i of a wave
+// instruction writes bytes [16 i, 16 i + 16) of a 1 KiB block (8 rows), so the swizzle is
+// applied to the SOURCE address of each lane.  The loads are written as inline assembly so
+// that the compiler does not serialise later LDS reads behind them; they are awaited with an
+// explicit vmcnt wait followed by a workgroup barrier.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_addr /* wave-uniform */) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gptr), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void wait_all_vmem() {
+    __builtin_amdgcn_s_waitcnt(0x0070 | 0x0f00);      // vmcnt(0); expcnt and lgkmcnt untouched
+}
 
 template <typename T, bool KTAIL>
 __global__ __launch_bounds__(kMineThreads, 1)
 void mine_tile_kernel(const MineArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     // two stage buffers, each: W rows then Z rows
-    unsigned char* stage0 = smem;
-    constexpr int kStageBuf = (kBM + kBN) * kRowStride;
+    constexpr int kStageBuf = (kBM + kBN) * kStageBytes;
     float* tau = reinterpret_cast<float*>(smem + 2 * kStageBuf);
     int* cnt = reinterpret_cast<int*>(tau + kBN);
     int* hist = cnt + kBN;                                   // [kMineWaves][256]
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) unsigned char*)smem));
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1;          // which 128-label half
     const int wn = wave >> 1;         // which 64-query quarter
     uint64_t* my_lists = a.lists + static_cast<size_t>(blockIdx.x) * kBN * kCandCap;
@@ -194,12 +215,20 @@ void mine_tile_kernel(const MineArgs a) {
         item = blockIdx.x; item_step = kMineGrid; item_end = a.nQT * a.S;
     }
 
-    const int row = tid >> 3;
-    const uint32_t kcol = (tid & 7) * 16;
-    // LDS addresses of this thread's fragments and stage chunks
-    const int frag_a = (wm * 128 + (lane & 31)) * kRowStride + (lane >> 5) * 16;
-    const int frag_b = kBM * kRowStride + (wn * 64 + (lane & 31)) * kRowStride + (lane >> 5) * 16;
-    const int st_off = row * kRowStride + static_cast<int>(kcol);
+    // ---- fragment reads: lane reads row (lane & 31) of a 32-row block, chunk 2 kk + (lane >> 5);
+    // the swizzle term of those rows is (lane >> 1) & 7, and the k-step enters as an xor of 32 kk
+    const int swz = (lane >> 1) & 7;
+    const int frag_a = (wm * 128 + (lane & 31)) * kStageBytes + (((lane >> 5) ^ swz) * 16);
+    const int frag_b = (kBM + wn * 64 + (lane & 31)) * kStageBytes + (((lane >> 5) ^ swz) * 16);
+
+    // ---- stage fill: waves 0..3 bring the W rows 64 (wave & 3) .. + 63, waves 4..7 the Z rows;
+    // instruction t of a wave covers rows 8 t .. 8 t + 7 of its 64, lane i -> row i / 8, position i % 8.
+    // The chunk a lane fetches is position ^ swizzle(row), which depends on t only through t & 1.
+    const bool dma_z = wave >= 4;
+    const int drow = (wave & 3) * 64 + (lane >> 3);
+    const uint32_t dcol[2] = {static_cast<uint32_t>(((lane & 7) ^ (lane >> 4)) * 16),
+                              static_cast<uint32_t>(((lane & 7) ^ ((lane >> 4) + 4)) * 16)};
+    const uint32_t dma_dst = lds_base + (dma_z ? kBM * kStageBytes : 0) + (wave & 3) * 64 * kStageBytes;
 
     for (; item < item_end; item += item_step) {
         const int64_t qtile = a.Qx > 0 ? item : item / a.S;
@@ -211,49 +240,37 @@ void mine_tile_kernel(const MineArgs a) {
         const int64_t q0 = qtile * kBN;
         if (tid < kBN) { tau[tid] = ordered_to_float(a.tau_g[q0 + tid]); cnt[tid] = 0; }
 
-        // byte offsets of this thread's four Z rows (rows past the end repeat the last row)
+        // ---- the load stream runs one stage ahead of the compute stream and stops at the last stage
         const unsigned char* zbase = a.Z + q0 * a.row_bytes;
-        uint32_t zoff[4];
-        {
-            const int64_t zlast = a.Zq - 1 - q0;
+        uint32_t roff[8];             // source byte offset of this lane's chunk, per instruction
+        auto set_rows = [&](int64_t last_row) {              // rows past the end repeat the last row
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int64_t r = row + 64 * it;
-                zoff[it] = static_cast<uint32_t>((r < zlast ? r : zlast) * a.row_bytes) + kcol;
+            for (int t = 0; t < 8; ++t) {
+                const int64_t r = drow + 8 * t;
+                roff[t] = static_cast<uint32_t>((r < last_row ? r : last_row) * a.row_bytes) + dcol[t & 1];
             }
-        }
-
-        // ---- the load stream runs two stages ahead of the compute stream and stops at the last stage
-        int64_t ld_tile = t_begin;
-        int ld_kb = 0;
-        StageRegs regs;
-        bool regs_ok = true;          // KTAIL: chunk lies inside the row
-        auto load_next = [&]() {
-            const int64_t l0 = ld_tile * kBM;
-            const unsigned char* wbase = a.W + l0 * a.row_bytes;
-            const int64_t wlast = a.L - 1 - l0;
-            uint32_t kb = static_cast<uint32_t>(ld_kb) * kStageBytes;
-            if (KTAIL) {
-                regs_ok = kb + kcol < static_cast<uint32_t>(a.row_bytes);
-                kb = regs_ok ? kb : 0u;                  // any valid address; the value is dropped
-            }
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int64_t r = row + 64 * it;
-                const uint32_t woff = static_cast<uint32_t>((r < wlast ? r : wlast) * a.row_bytes) + kcol;
-                regs.w[it] = *reinterpret_cast<const uint4*>(wbase + (woff + kb));
-                regs.z[it] = *reinterpret_cast<const uint4*>(zbase + (zoff[it] + kb));
-            }
-            if (++ld_kb == a.nkb) { ld_kb = 0; if (ld_tile + 1 < t_end) ++ld_tile; }
         };
-        auto store_regs = [&](unsigned char* buf) {
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                uint4 w = regs.w[it], z = regs.z[it];
-                if (KTAIL && !regs_ok) { w = make_uint4(0, 0, 0, 0); z = make_uint4(0, 0, 0, 0); }
-                *reinterpret_cast<uint4*>(buf + st_off + 64 * it * kRowStride) = w;
-                *reinterpret_cast<uint4*>(buf + kBM * kRowStride + st_off + 64 * it * kRowStride) = z;
+        if (dma_z) set_rows(a.Zq - 1 - q0);
+        int64_t ld_tile = t_begin;
+        int ld_kb = 0, ld_slot = 0;
+        int64_t to_issue = (t_end - t_begin) * a.nkb;
+        auto issue_stage = [&]() {
+            const unsigned char* base = zbase;
+            if (!dma_z) {
+                if (ld_kb == 0) set_rows(a.L - 1 - ld_tile * kBM);
+                base = a.W + ld_tile * kBM * a.row_bytes;
             }
+            const uint32_t kb = static_cast<uint32_t>(ld_kb) * kStageBytes;
+            const uint32_t dst = dma_dst + static_cast<uint32_t>(ld_slot) * kStageBuf;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const unsigned char* g = base + (roff[t] + kb);
+                if (KTAIL && kb + dcol[t & 1] >= static_cast<uint32_t>(a.row_bytes)) g = a.zeros;
+                lds_dma16(g, dst + t * 1024);
+            }
+            ld_slot ^= 1;
+            --to_issue;
+            if (++ld_kb == a.nkb) { ld_kb = 0; ++ld_tile; }
         };
 
         f32x16 acc[4][2];
@@ -264,75 +281,88 @@ void mine_tile_kernel(const MineArgs a) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.0f;
 
-        load_next();
-        __syncthreads();                                     // tau/cnt visible; LDS free
-        store_regs(stage0);
-        load_next();
-        __syncthreads();
+        __syncthreads();                                     // tau/cnt visible; both stage buffers free
+        issue_stage();
 
         int buf_sel = 0;
         for (int64_t tile = t_begin; tile < t_end; ++tile) {
             for (int kb = 0; kb < a.nkb; ++kb) {
-                const unsigned char* cur = stage0 + buf_sel * kStageBuf;
+                wait_all_vmem();                             // this wave's part of the stage has landed
+                __syncthreads();                             // everyone's has; the other buffer is free
+                if (to_issue > 0) issue_stage();
+                const unsigned char* cur = smem + buf_sel * kStageBuf;
                 buf_sel ^= 1;
-                // the other buffer was last read before the barrier that ended the previous stage
-                store_regs(stage0 + buf_sel * kStageBuf);
-                __builtin_amdgcn_sched_barrier(0);           // keep the global loads of stage s+2 ahead
-                load_next();                                 // of this stage's MFMAs: they need its whole
-                __builtin_amdgcn_sched_barrier(0);           // duration to arrive
-
-                uint4 fa[2][4], fb[2][2];
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-                    fa[0][mt] = *reinterpret_cast<const uint4*>(cur + frag_a + mt * 32 * kRowStride);
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    fb[0][nt] = *reinterpret_cast<const uint4*>(cur + frag_b + nt * 32 * kRowStride);
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    if (kk < 3) {                            // fragments of the next K sub-step
+                    uint4 fa[4], fb[2];
 #pragma unroll
-                        for (int mt = 0; mt < 4; ++mt)
-                            fa[(kk + 1) & 1][mt] = *reinterpret_cast<const uint4*>(
-                                cur + frag_a + mt * 32 * kRowStride + (kk + 1) * 32);
+                    for (int mt = 0; mt < 4; ++mt)
+                        fa[mt] = *reinterpret_cast<const uint4*>(cur + ((frag_a ^ (kk * 32)) + mt * 32 * kStageBytes));
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt)
-                            fb[(kk + 1) & 1][nt] = *reinterpret_cast<const uint4*>(
-                                cur + frag_b + nt * 32 * kRowStride + (kk + 1) * 32);
-                    }
+                    for (int nt = 0; nt < 2; ++nt)
+                        fb[nt] = *reinterpret_cast<const uint4*>(cur + ((frag_b ^ (kk * 32)) + nt * 32 * kStageBytes));
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
                         for (int nt = 0; nt < 2; ++nt)
-                            MineTraits<T>::mma(fa[kk & 1][mt], fb[kk & 1][nt], acc[mt][nt]);
+                            MineTraits<T>::mma(fa[mt], fb[nt], acc[mt][nt]);
                 }
-                if (kb + 1 < a.nkb) __syncthreads();
             }
 
-            // ---- threshold filter: lane owns query column (lane & 31) of each N tile
+            // ---- threshold filter: lane owns query column (lane & 31) of each N tile.  A score that
+            // passes is first parked, with its query and row, in this wave's stash: the slot comes
+            // from a ballot and a wave-uniform fill count, so nothing waits on an atomic.  The stash
+            // lives in the stage buffer that was read last (no load is in flight into it until the
+            // next tile's second stage) and is emptied 64 entries at a time into the per-query lists.
+            __syncthreads();                                 // every wave has finished reading that buffer
+            uint2* stash = reinterpret_cast<uint2*>(smem + (buf_sel ^ 1) * kStageBuf) + wave * kStash;
             const int64_t l0 = tile * kBM;
+            int fill = 0;
+            auto flush = [&]() {
+                for (int e = lane; e < fill; e += kWave) {
+                    const uint2 en = stash[e];
+                    const int q = static_cast<int>(en.y >> 8);
+                    const int64_t lab = l0 + (en.y & 255u);
+                    if (lab < a.L) {                         // rows past the end repeat the last row
+                        const int slot = atomicAdd(&cnt[q], 1);
+                        my_lists[static_cast<size_t>(q) * kCandCap + slot] =
+                            make_key(__uint_as_float(en.x) + 0.0f /* -0 -> +0 */, static_cast<int32_t>(lab));
+                    }
+                }
+                fill = 0;
+            };
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) {
                 const int qloc = wn * 64 + nt * 32 + (lane & 31);
-                const float t = tau[qloc];
-                const bool qok = (q0 + qloc) < a.Zq;
+                const float t = (q0 + qloc) < a.Zq ? tau[qloc] : INFINITY;
                 float mx = acc[0][nt][0];
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[mt][nt][i]);
-                if (__ballot(qok && mx >= t) != 0ull) {
-                    uint64_t* list = my_lists + static_cast<size_t>(qloc) * kCandCap;
+                if (__ballot(mx >= t) != 0ull) {
+                    uint32_t qrow = static_cast<uint32_t>((qloc << 8) | (4 * (lane >> 5)));
+                    asm volatile("" : "+v"(qrow));           // keep the 64 row words out of registers
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
                         for (int i = 0; i < 16; ++i) {
-                            const int64_t lab = l0 + wm * 128 + mt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-                            const float v = acc[mt][nt][i] + 0.0f;     // -0 -> +0
-                            if (qok && lab < a.L && v >= t) {
-                                const int slot = atomicAdd(&cnt[qloc], 1);
-                                list[slot] = make_key(v, static_cast<int32_t>(lab));
+                            const float v = acc[mt][nt][i];
+                            const bool hit = v >= t;
+                            const uint64_t m = __ballot(hit);
+                            if (__builtin_expect(m != 0ull, 0)) {        // out of line: a taken branch costs more
+                                if (hit) {
+                                    const int pos = fill + static_cast<int>(__builtin_amdgcn_mbcnt_hi(
+                                        static_cast<uint32_t>(m >> 32),
+                                        __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u)));
+                                    stash[pos] = make_uint2(
+                                        __float_as_uint(v),
+                                        qrow + static_cast<uint32_t>(wm * 128 + mt * 32 + 8 * (i >> 2) + (i & 3)));
+                                }
+                                fill += __popcll(m);
                             }
+                            // 8 values add at most 512 entries
+                            if ((i & 7) == 7 && fill > kStash - 8 * kWave) flush();
                         }
                     }
                 }
@@ -341,6 +371,7 @@ void mine_tile_kernel(const MineArgs a) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.0f;
             }
+            if (fill > 0) flush();
             __syncthreads();
 
             // ---- wave w looks after queries 32w..32w+31.  A list that could overflow during the
@@ -360,26 +391,49 @@ void mine_tile_kernel(const MineArgs a) {
                         todo &= todo - 1;
                         const int qsel = wave * 32 + src;
                         const int nsel = __shfl(n, src, kWave);
+                        uint64_t* lsel = my_lists + static_cast<size_t>(qsel) * kCandCap;
                         const float t = wave_select_k<kCandCap / kWave>(
-                            my_lists + static_cast<size_t>(qsel) * kCandCap, nsel, a.k, hist + wave * 256);
+                            lsel, [lsel](int idx) { return lsel[idx]; }, nsel, a.k, hist + wave * 256);
                         if (lane == src) { t_new = t; n = a.k; }
                     }
                     if (want) { tau[qloc] = fmaxf(tau[qloc], t_new); cnt[qloc] = n; }
                     if (last) {
                         // ---- close the slice: append the survivors to the global list of each query
                         int base = 0;
-                        if (lane < 32 && qok && n > 0) base = atomicAdd(&a.gcnt[q0 + qloc], n);
-                        uint64_t some = __ballot(lane < 32 && qok && n > 0);
-                        while (some) {
-                            const int src = __ffsll(static_cast<long long>(some)) - 1;
-                            some &= some - 1;
-                            const int nsel = __shfl(n, src, kWave);
-                            const int bsel = __shfl(base, src, kWave);
-                            const int qsel = wave * 32 + src;
-                            const uint64_t* list = my_lists + static_cast<size_t>(qsel) * kCandCap;
-                            uint64_t* out = a.glist + static_cast<size_t>(q0 + qsel) * a.glist_cap;
-                            for (int e = lane; e < nsel; e += kWave)
-                                if (bsel + e < a.glist_cap) out[bsel + e] = list[e];
+                        const bool have = lane < 32 && qok && n > 0;
+                        if (have) base = atomicAdd(&a.gcnt[q0 + qloc], n);
+                        if (__ballot(have && n > 16) == 0ull) {
+                            // short lists (the usual case): lanes l and l + 32 copy the list of query l,
+                            // even and odd entries, all loads issued before the stores
+                            const int nq = __shfl(have ? n : 0, lane & 31, kWave);
+                            const int bq = __shfl(base, lane & 31, kWave);
+                            const int ql = wave * 32 + (lane & 31);
+                            const uint64_t* list = my_lists + static_cast<size_t>(ql) * kCandCap;
+                            uint64_t* out = a.glist + static_cast<size_t>(q0 + ql) * a.glist_cap + bq;
+                            uint64_t v[8];
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                const int e = (lane >> 5) + 2 * j;
+                                v[j] = e < nq ? list[e] : 0ull;
+                            }
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                const int e = (lane >> 5) + 2 * j;
+                                if (e < nq && bq + e < a.glist_cap) out[e] = v[j];
+                            }
+                        } else {
+                            uint64_t some = __ballot(have);
+                            while (some) {
+                                const int src = __ffsll(static_cast<long long>(some)) - 1;
+                                some &= some - 1;
+                                const int nsel = __shfl(n, src, kWave);
+                                const int bsel = __shfl(base, src, kWave);
+                                const int qsel = wave * 32 + src;
+                                const uint64_t* list = my_lists + static_cast<size_t>(qsel) * kCandCap;
+                                uint64_t* out = a.glist + static_cast<size_t>(q0 + qsel) * a.glist_cap;
+                                for (int e = lane; e < nsel; e += kWave)
+                                    if (bsel + e < a.glist_cap) out[bsel + e] = list[e];
+                            }
                         }
                     }
                 }
@@ -389,9 +443,10 @@ void mine_tile_kernel(const MineArgs a) {
     }
 }
 
-__global__ void mine_init_kernel(uint32_t* tau_g, int32_t* gcnt, int64_t n) {
+__global__ void mine_init_kernel(uint32_t* tau_g, int32_t* gcnt, int64_t n, uint32_t* zeros /* [64] */) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < n) { tau_g[i] = kTauInit; gcnt[i] = 0; }
+    if (i < 64) zeros[i] = 0u;
 }
 
 // ---------------------------------------------------------------------------
@@ -483,8 +538,9 @@ void mine_select_kernel(uint64_t* __restrict__ glist, int32_t* __restrict__ gcnt
     int n = gcnt[q];
     n = n < glist_cap ? n : glist_cap;
     if (n > k) {
-        const float t = (n <= kSelectRegs * kWave) ? wave_select_k<kSelectRegs>(list, n, k, hist[wave])
-                                                   : wave_select_stream(list, n, k, hist[wave]);
+        const float t = (n <= kSelectRegs * kWave)
+                            ? wave_select_k<kSelectRegs>(list, [list](int idx) { return list[idx]; }, n, k, hist[wave])
+                            : wave_select_stream(list, n, k, hist[wave]);
         n = k;
         if (lane == 0) { gcnt[q] = k; tau_g[q] = float_to_ordered(t); }
     }
@@ -518,11 +574,11 @@ void mine_select_kernel(uint64_t* __restrict__ glist, int32_t* __restrict__ gcnt
 struct MinePlan {
     int64_t nQT, nLT;
     int kcap, nkb, glist_cap;
-    size_t off_lists, off_glist, off_gcnt, off_tau, ws_bytes;
+    size_t off_lists, off_glist, off_gcnt, off_tau, off_zero, ws_bytes;
     size_t lds_tile;
 };
 
-static int slices_cap(int kcap) { return kcap <= 64 ? 64 : 32; }    // slices per phase at most
+static int slices_cap(int kcap) { return kcap <= 64 ? kMaxSlices : kMaxSlices / 2; }    // slices per phase at most
 
 static int plan_mine(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, MinePlan* p) {
     if (t != XC_F32 && t != XC_BF16) return XC_EINVAL;
@@ -545,8 +601,9 @@ static int plan_mine(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, MinePlan
     p->off_glist = take(nq * p->glist_cap * sizeof(uint64_t));
     p->off_gcnt = take(nq * sizeof(int32_t));
     p->off_tau = take(nq * sizeof(uint32_t));
+    p->off_zero = take(256);
     p->ws_bytes = off;
-    p->lds_tile = 2 * static_cast<size_t>(kBM + kBN) * kRowStride + kBN * 8 + kMineWaves * 256 * 4;
+    p->lds_tile = 2 * static_cast<size_t>(kBM + kBN) * kStageBytes + kBN * 8 + kMineWaves * 256 * 4;
     return XC_OK;
 }
 
@@ -586,6 +643,7 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
     a.gcnt = reinterpret_cast<int32_t*>(w8 + p.off_gcnt);
     uint32_t* tau_g = reinterpret_cast<uint32_t*>(w8 + p.off_tau);
     a.tau_g = tau_g;
+    a.zeros = w8 + p.off_zero;
 
     static bool attr_done = false;       // raise the dynamic LDS limit once per process
     if (!attr_done) {
@@ -599,7 +657,8 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
         attr_done = true;
     }
     const int64_t nq = p.nQT * kBN;
-    mine_init_kernel<<<dim3(static_cast<unsigned>((nq + 255) / 256)), 256, 0, st>>>(tau_g, a.gcnt, nq);
+    mine_init_kernel<<<dim3(static_cast<unsigned>((nq + 255) / 256)), 256, 0, st>>>(tau_g, a.gcnt, nq,
+                                                                                        reinterpret_cast<uint32_t*>(w8 + p.off_zero));
     XC_HIP_CHECK(hipGetLastError());
 
     int64_t lo = 0;
