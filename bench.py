@@ -236,6 +236,29 @@ def main():
         "roofline": roofline,
         "kernels_us": {n: round(k["avg_us"], 2) for n, k in kernels.items()},
     }
+    # ---- what the chip sustains on two trivial kernels (context for the fractions above) -----
+    achievable = {}
+    if not args.no_profile_pass:
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for rnd in (0, 1):
+            binding.mfma_probe(2000, bool(rnd))                     # warm-up
+            ev[0].record()
+            flop = sum(binding.mfma_probe(4000, bool(rnd)) for _ in range(5))
+            ev[1].record()
+            torch.cuda.synchronize()
+            achievable["mfma_bf16_%s_operands_TFLOPs" % ("random" if rnd else "zero")] = flop / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e12
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        binding.copy_probe(b, a)
+        ev[2].record()
+        for _ in range(5):
+            binding.copy_probe(b, a)
+        ev[3].record()
+        torch.cuda.synchronize()
+        achievable["copy_GBs_read_plus_write"] = 5 * 2.0 * a.numel() / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e9
+        del a, b
+    result["achievable"] = achievable
+
     if "mine_tile" in kernels:
         per_call_ms = (kernels["mine_tile"]["total_ms"] + kernels.get("mine_select", {"total_ms": 0})["total_ms"]) / max(mines, 1)
         result["mine_pairs_per_s"] = pool * wl.L / (per_call_ms * 1e-3)

@@ -145,6 +145,15 @@ int xc_profile_reset(void);
  * `stream`.  XC_EINVAL on null or misaligned arguments. */
 int xc_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Measurement aid: a register-resident loop of bf16 MFMA instructions (no memory traffic) on
+ * 256 workgroups of 8 waves, `iters` (1 .. 2^20) rounds of 8 products per wave.  With
+ * random_operands != 0 the operands are pseudo-random bf16 values, else zero: the rate the chip
+ * sustains depends on the operand values through its power limit, and the benchmark reports it
+ * beside the published peak.  `out` is device memory for 256*512 floats (a checksum, so that the
+ * loop is not removed); `*flop` (host pointer, may be NULL) receives the floating-point
+ * operations of one launch.  Asynchronous on `stream`. */
+int xc_mfma_probe(float* out, int iters, int random_operands, double* flop, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,6 +35,7 @@ _SIGNATURES = {
                               ctypes.POINTER(ctypes.c_int64)]),
     "xc_profile_reset": (_i32, []),
     "xc_copy_probe": (_i32, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "xc_mfma_probe": (_i32, [ctypes.c_void_p, _i32, _i32, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]),
     "xc_step": (_i32, [_ptr, _ptr, _i64, _i64, _i32, _ptr, _i32, _ptr, _ptr, _i32, _f32, _i32, _i32,
                        _ptr, _ptr, _ptr, _ptr, _ptr, _ptr, ctypes.c_size_t, _ptr]),
 }
@@ -224,3 +225,12 @@ def copy_probe(dst, src) -> None:
         raise ValueError("copy_probe: sizes differ")
     _check(load_library().xc_copy_probe(_dev(dst, torch.uint8, "dst"), _dev(src, torch.uint8, "src"),
                                         src.numel(), _stream()), "xc_copy_probe")
+
+
+def mfma_probe(iters: int, random_operands: bool) -> float:
+    """Launch the register-resident MFMA loop once; returns the flop of the launch."""
+    out = torch.empty(256 * 512, dtype=torch.float32, device="cuda:0")
+    flop = ctypes.c_double()
+    _check(load_library().xc_mfma_probe(_dev(out, torch.float32, "out"), int(iters), 1 if random_operands else 0,
+                                        ctypes.byref(flop), _stream()), "xc_mfma_probe")
+    return flop.value

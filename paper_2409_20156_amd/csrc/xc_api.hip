@@ -52,7 +52,63 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(uint4* __restrict__ dst
         dst[i] = src[i];
 }
 
+// Register-resident MFMA loop: 8 independent 32x32x16 bf16 products per iteration and wave,
+// operands either zero or pseudo-random bf16 values in [0.25, 0.5) with random sign.  No memory
+// traffic inside the loop; used to measure the MFMA rate the chip sustains (it depends on the
+// operand values through the power limit).
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int kProbeGrid = 256, kProbeThreads = 512;
+__global__ __launch_bounds__(kProbeThreads, 1) void mfma_probe_kernel(float* out, int iters, int random_operands) {
+    probe_f32x16 acc[8];
+#pragma unroll
+    for (int n = 0; n < 8; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[n][i] = 0.0f;
+    uint4 fa[4], fb[2];
+#pragma unroll
+    for (int m = 0; m < 6; ++m) {
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t r = threadIdx.x * 977u + blockIdx.x * 131071u + m * 17u + j;
+            r ^= r >> 16; r *= 0x7feb352du; r ^= r >> 15; r *= 0x846ca68bu; r ^= r >> 16;
+            const uint32_t lo = 0x3e80u | (r & 0x807fu), hi = 0x3e80u | ((r >> 16) & 0x807fu);
+            w[j] = random_operands ? (lo | (hi << 16)) : 0u;
+        }
+        const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
+        if (m < 4) fa[m] = v; else fb[m - 4] = v;
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                probe_bf16x8 av, bv;
+                __builtin_memcpy(&av, &fa[mt], 16);
+                __builtin_memcpy(&bv, &fb[nt], 16);
+                acc[mt * 2 + nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[mt * 2 + nt], 0, 0, 0);
+            }
+        if (random_operands) { fa[0].x ^= 0x00010001u; fb[1].y ^= 0x00010001u; }   // keep the inputs changing
+    }
+    float tot = 0.0f;
+#pragma unroll
+    for (int n = 0; n < 8; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) tot += acc[n][i];
+    out[blockIdx.x * kProbeThreads + threadIdx.x] = tot;
+}
+
 }  // namespace xc
+
+extern "C" int xc_mfma_probe(float* out, int iters, int random_operands, double* flop, void* stream) {
+    if (!out || iters < 1 || iters > (1 << 20)) return XC_EINVAL;
+    xc::mfma_probe_kernel<<<xc::kProbeGrid, xc::kProbeThreads, 0, static_cast<hipStream_t>(stream)>>>(
+        out, iters, random_operands);
+    XC_HIP_CHECK(hipGetLastError());
+    if (flop) *flop = 2.0 * 32 * 32 * 16 * 8.0 * iters * (xc::kProbeThreads / 64) * xc::kProbeGrid;
+    return XC_OK;
+}
 
 extern "C" int xc_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
     if (!dst || !src || (bytes & 15) || ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15))

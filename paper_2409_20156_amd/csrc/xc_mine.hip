@@ -319,14 +319,30 @@ void mine_tile_kernel(const MineArgs a) {
             const int64_t l0 = tile * kBM;
             int fill = 0;
             auto flush = [&]() {
-                for (int e = lane; e < fill; e += kWave) {
-                    const uint2 en = stash[e];
-                    const int q = static_cast<int>(en.y >> 8);
-                    const int64_t lab = l0 + (en.y & 255u);
-                    if (lab < a.L) {                         // rows past the end repeat the last row
-                        const int slot = atomicAdd(&cnt[q], 1);
-                        my_lists[static_cast<size_t>(q) * kCandCap + slot] =
-                            make_key(__uint_as_float(en.x) + 0.0f /* -0 -> +0 */, static_cast<int32_t>(lab));
+                // four batches of 64 entries at a time, so that the slot atomics overlap
+                for (int e0 = 0; e0 < fill; e0 += 4 * kWave) {
+                    uint2 en[4];
+                    int slot[4];
+                    bool ok[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int e = e0 + u * kWave + lane;
+                        ok[u] = e < fill;
+                        en[u] = ok[u] ? stash[e] : make_uint2(0u, 0u);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        if (e0 + u * kWave >= fill) break;                     // uniform
+                        ok[u] = ok[u] && (l0 + (en[u].y & 255u) < a.L);      // rows past the end repeat the last row
+                        slot[u] = ok[u] ? atomicAdd(&cnt[en[u].y >> 8], 1) : 0;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        if (e0 + u * kWave >= fill) break;
+                        if (ok[u])
+                            my_lists[static_cast<size_t>(en[u].y >> 8) * kCandCap + slot[u]] =
+                                make_key(__uint_as_float(en[u].x) + 0.0f /* -0 -> +0 */,
+                                         static_cast<int32_t>(l0 + (en[u].y & 255u)));
                     }
                 }
                 fill = 0;
@@ -422,17 +438,28 @@ void mine_tile_kernel(const MineArgs a) {
                                 if (e < nq && bq + e < a.glist_cap) out[e] = v[j];
                             }
                         } else {
-                            uint64_t some = __ballot(have);
-                            while (some) {
-                                const int src = __ffsll(static_cast<long long>(some)) - 1;
-                                some &= some - 1;
-                                const int nsel = __shfl(n, src, kWave);
-                                const int bsel = __shfl(base, src, kWave);
-                                const int qsel = wave * 32 + src;
-                                const uint64_t* list = my_lists + static_cast<size_t>(qsel) * kCandCap;
-                                uint64_t* out = a.glist + static_cast<size_t>(q0 + qsel) * a.glist_cap;
-                                for (int e = lane; e < nsel; e += kWave)
-                                    if (bsel + e < a.glist_cap) out[bsel + e] = list[e];
+                            // long lists (dense early phases): 64 entries of 8 queries per round,
+                            // loads before stores
+                            const int nv = have ? n : 0;
+                            for (int c0 = 0; __ballot(nv > c0) != 0ull; c0 += kWave) {
+                                const int e = c0 + lane;
+                                for (int qb = 0; qb < 32; qb += 8) {
+                                    uint64_t v[8];
+                                    int dst[8];
+#pragma unroll
+                                    for (int u = 0; u < 8; ++u) {
+                                        const int nsel = __shfl(nv, qb + u, kWave);
+                                        const int bsel = __shfl(base, qb + u, kWave);
+                                        dst[u] = (e < nsel && bsel + e < a.glist_cap) ? bsel + e : -1;
+                                        v[u] = dst[u] >= 0
+                                                   ? my_lists[static_cast<size_t>(wave * 32 + qb + u) * kCandCap + e]
+                                                   : 0ull;
+                                    }
+#pragma unroll
+                                    for (int u = 0; u < 8; ++u)
+                                        if (dst[u] >= 0)
+                                            a.glist[static_cast<size_t>(q0 + wave * 32 + qb + u) * a.glist_cap + dst[u]] = v[u];
+                                }
                             }
                         }
                     }

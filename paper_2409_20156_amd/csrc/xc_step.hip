@@ -634,13 +634,17 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
     const int64_t row_bytes = static_cast<int64_t>(d) * sizeof(T);
     const unsigned char* Zb = reinterpret_cast<const unsigned char*>(Z);
     const int64_t n_seg = n_touched[0];
-    // a group walks several segments so that waves live long enough to keep the chip full
-    for (int64_t s = static_cast<int64_t>(blockIdx.x) * NG + tid / G; s < n_seg;
-         s += static_cast<int64_t>(gridDim.x) * NG) {
-    // hop 1: everything that identifies the segment
-    const int p0 = seg_start[s], p1 = seg_start[s + 1];
-    const int64_t label = touched[s];
-    const uint32_t idx0 = seg_idx0[s];
+    // a group walks several segments so that waves live long enough to keep the chip full;
+    // hop 1 (everything that identifies a segment) is fetched one segment ahead
+    const int64_t s_step = static_cast<int64_t>(gridDim.x) * NG;
+    int64_t s = static_cast<int64_t>(blockIdx.x) * NG + tid / G;
+    int p0_n = 0, p1_n = 0, label_n = 0;
+    uint32_t idx0_n = 0;
+    if (s < n_seg) { p0_n = seg_start[s]; p1_n = seg_start[s + 1]; label_n = touched[s]; idx0_n = seg_idx0[s]; }
+    for (; s < n_seg; s += s_step) {
+    const int p0 = p0_n, p1 = p1_n;
+    const int64_t label = label_n;
+    const uint32_t idx0 = idx0_n;
 
     // pair index -> query row: exact division by n through a multiply-high (n_magic, n_shift
     // from the host; valid for every index below 2^31)
@@ -666,6 +670,11 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
                 z0[j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
             }
         }
+    }
+
+    if (s + s_step < n_seg) {
+        const int64_t sn = s + s_step;
+        p0_n = seg_start[sn]; p1_n = seg_start[sn + 1]; label_n = touched[sn]; idx0_n = seg_idx0[sn];
     }
 
     float acc[CPL][EPC];
