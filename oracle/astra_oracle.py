@@ -20,6 +20,9 @@ xc_step             Eq. 2 (sampled BCE) with its analytic gradient (form given
                     W from Alg. 1; loss averaged over data points (Sec. 4).
                     A soft-max variant with proposal-corrected logits is the
                     second loss kind.
+train_schedule      the outer loop of Alg. 1 over the three functions above:
+                    warm-up steps with uniform negatives while t < tau_s, then a
+                    shortlist refresh every tau_r steps and hard+random steps.
 full_bce_loss       Eq. 1, every one of the L labels, for pinning Eq. 2.
 full_softmax_loss   plain soft-max cross-entropy over all L labels.
 
@@ -280,6 +283,43 @@ def xc_step(Z, W, pos, neg, logq, lr: float, kind: int = LOSS_BCE,
 # --------------------------------------------------------------------------
 # full-label references (tiny inputs only, O(B L d))
 # --------------------------------------------------------------------------
+def train_schedule(Z_pool, W, pos_pool, B: int, k_h: int, k_r: int, steps: int, tau_s: int, tau_r: int,
+                   lr: float, seeds, kind: int = LOSS_BCE, storage: str = "f32"):
+    """Alg. 1 for the classifier alone (encoder frozen: the query pool Z_pool is fixed).
+
+    Step t uses the mini-batch of rows (t mod nbatch)*B .. +B of the pool.  While t < tau_s the
+    negatives are all uniform (warm-up).  From t = tau_s on, the shortlists of the WHOLE pool are
+    rebuilt by exact search with the current W whenever (t - tau_s) is a multiple of tau_r, and
+    the step takes its batch's rows of the (possibly stale) shortlist as hard negatives plus k_r
+    uniform ones.  seeds[t] is the sampler's seed of step t.  W (float64 [L,d]) is updated in
+    place, rounded to `storage` after every step as the stored matrix is.
+
+    Returns a dict: loss (list, per step), neg (list, per step: the sampled ids), shortlists (list of (t, int32 [pool,k_h]) per refresh),
+    overlap (list, per refresh after the first: mean over queries of |fresh & stale| / k_h).
+    """
+    pool, L = Z_pool.shape[0], W.shape[0]
+    nbatch = max(1, pool // B)
+    out = {"loss": [], "shortlists": [], "overlap": [], "neg": []}
+    shortlist = None
+    for t in range(steps):
+        if t >= tau_s and (t - tau_s) % tau_r == 0:
+            fresh, _ = mine_negatives(Z_pool, W, k_h)
+            if shortlist is not None:
+                same = [len(set(fresh[q].tolist()) & set(shortlist[q].tolist())) for q in range(pool)]
+                out["overlap"].append(float(np.mean(same)) / k_h)
+            shortlist = fresh
+            out["shortlists"].append((t, fresh.copy()))
+        b = t % nbatch
+        lo, hi = b * B, (b + 1) * B
+        rows = shortlist[lo:hi] if shortlist is not None else None
+        neg, logq = sample_negatives(rows, B, k_h, k_r, L, seeds[t])
+        res = xc_step(Z_pool[lo:hi], W, pos_pool[lo:hi], neg, logq, lr, kind=kind, storage=storage)
+        W[res["touched"]] = res["W_rows"]
+        out["loss"].append(res["loss"])
+        out["neg"].append(neg)
+    return out
+
+
 def full_bce_loss(Z, W, pos):
     """Eq. 1 averaged over the batch: every label is either a positive of the
     query (first sum) or a negative (second sum)."""

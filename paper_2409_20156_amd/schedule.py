@@ -1,0 +1,67 @@
+"""Outer loop of Alg. 1 over the three library calls (classifier only, fixed query pool).
+
+Argument marshalling and the step counter only: warm-up steps with uniform negatives while
+t < tau_s, then a refresh of the whole pool's shortlists every tau_r steps (xc_mine_negatives
+with the current W) and hard + random steps (xc_sample_negatives, xc_step).  All buffers are
+allocated once, before the first step.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as xc
+
+
+class Schedule:
+    def __init__(self, Z_pool: torch.Tensor, W: torch.Tensor, pos_pool: torch.Tensor, B: int, k_h: int,
+                 k_r: int, tau_s: int, tau_r: int, lr: float, kind: int = xc.XC_LOSS_BCE):
+        self.Z, self.W, self.pos = Z_pool, W, pos_pool
+        self.B, self.k_h, self.k_r, self.tau_s, self.tau_r, self.lr, self.kind = B, k_h, k_r, tau_s, tau_r, lr, kind
+        dev = W.device
+        pool, d = Z_pool.shape
+        L = W.shape[0]
+        self.pool, self.L = pool, L
+        self.nbatch = max(1, pool // B)
+        code = xc.XC_F32 if W.dtype == torch.float32 else xc.XC_BF16
+        n_neg = k_h + k_r
+        k_p = pos_pool.shape[1]
+        self.mine_ws = torch.empty(xc.mine_workspace(pool, L, d, k_h, code), dtype=torch.uint8, device=dev)
+        self.step_ws = torch.empty(xc.step_workspace(B, d, k_p, n_neg, code), dtype=torch.uint8, device=dev)
+        self.shortlist = [torch.empty((pool, k_h), dtype=torch.int32, device=dev) for _ in range(2)]
+        self.cur = -1                                  # index of the valid shortlist buffer, -1 = none yet
+        self.neg = torch.empty((B, n_neg), dtype=torch.int32, device=dev)
+        self.logq = torch.empty((B, n_neg), dtype=torch.float32, device=dev)
+        P = B * (k_p + n_neg)
+        self.out = {"loss": torch.empty(1, dtype=torch.float32, device=dev),
+                    "dZ": torch.empty((B, d), dtype=torch.float32, device=dev),
+                    "touched": torch.empty(P, dtype=torch.int32, device=dev),
+                    "n_touched": torch.empty(1, dtype=torch.int32, device=dev)}
+        self.t = 0
+        self.refreshed = False                         # the last step() call rebuilt the shortlists
+
+    def stale_and_fresh(self):
+        """(previous, current) shortlist tensors after a refresh that had a predecessor, else None."""
+        if self.cur < 0 or not self.had_previous:
+            return None
+        return self.shortlist[1 - self.cur], self.shortlist[self.cur]
+
+    had_previous = False
+
+    def step(self, seed: int):
+        t = self.t
+        self.refreshed = False
+        if t >= self.tau_s and (t - self.tau_s) % self.tau_r == 0:
+            nxt = 0 if self.cur < 0 else 1 - self.cur
+            xc.mine_negatives(self.Z, self.W, self.k_h, workspace=self.mine_ws, out=self.shortlist[nxt])
+            self.had_previous = self.cur >= 0
+            self.cur = nxt
+            self.refreshed = True
+        b = t % self.nbatch
+        lo, hi = b * self.B, (b + 1) * self.B
+        rows = self.shortlist[self.cur][lo:hi] if self.cur >= 0 else None
+        xc.sample_negatives(rows, self.k_h, self.k_r, self.L, seed, B=self.B, device=self.W.device,
+                            neg=self.neg, logq=self.logq)
+        xc.xc_step(self.Z[lo:hi], self.W, self.pos[lo:hi], self.neg, self.logq, self.lr, kind=self.kind,
+                   workspace=self.step_ws, out=self.out)
+        self.t += 1
+        return self.out

@@ -1,0 +1,50 @@
+"""GPU parity of the outer loop of Alg. 1 (warm-up, periodic refresh, hard + random steps):
+the library driven by paper_2409_20156_amd.schedule against the oracle's train_schedule, each on
+its own copy of the same generated inputs (no state is copied between the two)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import astra_oracle as orc
+from paper_2409_20156_amd import synth
+from tests.parity import TOL, check_rows_close, check_topk, f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.parametrize("kind", [orc.LOSS_BCE, orc.LOSS_SOFTMAX])
+def test_schedule_matches_oracle(kind):
+    from paper_2409_20156_amd.schedule import Schedule
+    L, d, B, pool, k_p, k_h, k_r = 4096, 64, 32, 64, 2, 8, 16
+    steps, tau_s, tau_r, lr = 7, 1, 2, 0.3
+    W = synth.make_matrix(11, synth.TAG_W, L, d, torch.float32, DEV)
+    Z = synth.make_matrix(11, synth.TAG_Z, pool, d, torch.float32, DEV)
+    pos = synth.zipf_positives(11, pool, L, 1.0, "uniform:1:2", k_p)
+    Z = synth.add_positive_signal(Z, W, pos)
+    seeds = [synth.step_seed(synth.BASE_SEED, 9, t) for t in range(steps)]
+    W64, Z64 = f64(W), f64(Z)
+    ref = orc.train_schedule(Z64, W64, pos, B, k_h, k_r, steps, tau_s, tau_r, lr, seeds, kind=kind, storage="f32")
+
+    sch = Schedule(Z, W, torch.tensor(pos, device=DEV), B, k_h, k_r, tau_s, tau_r, lr, kind=kind)
+    tol = 20 * TOL["f32"]                  # rounding differences compound over the steps
+    n_ref, overlaps = 0, []
+    for t in range(steps):
+        out = sch.step(seeds[t])
+        torch.cuda.synchronize()
+        loss = float(out["loss"].item())
+        assert abs(loss - ref["loss"][t]) <= tol * abs(ref["loss"][t]), (t, loss, ref["loss"][t])
+        if sch.refreshed:
+            t_ref, sl_ref = ref["shortlists"][n_ref]
+            assert t_ref == t
+            got = sch.shortlist[sch.cur].cpu().numpy()
+            assert (np.sort(got, axis=1) == np.sort(sl_ref, axis=1)).all(), "refresh at step %d" % t
+            pair = sch.stale_and_fresh()
+            if pair is not None:
+                stale, fresh = (x.cpu().numpy() for x in pair)
+                overlaps.append(np.mean([len(set(fresh[q]) & set(stale[q])) for q in range(pool)]) / k_h)
+            n_ref += 1
+    assert n_ref == len(ref["shortlists"]) == 3
+    assert np.allclose(overlaps, ref["overlap"], atol=1e-12)
+    assert 0.0 < min(overlaps) and max(overlaps) < 1.0      # the refresh did change the lists
+    check_rows_close(f64(W), W64, tol, "W after the schedule")

@@ -328,3 +328,60 @@ def test_storage_rounding_of_updated_rows():
     b = orc.xc_step(Zb, Wb, pos, neg, logq, 0.1, storage="bf16")
     assert (b["W_rows"] == orc.round_to_bf16(a["W_rows"])).all()
     assert np.abs(b["W_rows"] - a["W_rows"]).max() <= np.abs(a["W_rows"]).max() * 2.0 ** -8
+
+
+# ---------------------------------------------------------------------------
+# outer loop of Alg. 1 (warm-up, refresh every tau_r steps, stale hard negatives)
+# ---------------------------------------------------------------------------
+def _schedule_inputs(seed=3, L=200, d=8, pool=12):
+    rng = np.random.default_rng(seed)
+    # float32-representable, as the stored matrices are
+    W = (rng.normal(size=(L, d)) / np.sqrt(d)).astype(np.float32).astype(np.float64)
+    Z = (rng.normal(size=(pool, d)) / np.sqrt(d)).astype(np.float32).astype(np.float64)
+    pos = rng.integers(0, L, size=(pool, 1)).astype(np.int32)
+    return W, Z, pos
+
+
+def test_schedule_refresh_times_and_stale_hard_negatives():
+    W, Z, pos = _schedule_inputs()
+    B, k_h, k_r, steps, tau_s, tau_r = 4, 3, 5, 9, 2, 3
+    out = orc.train_schedule(Z, W.copy(), pos, B, k_h, k_r, steps, tau_s, tau_r, 0.5, list(range(100, 100 + steps)))
+    assert [t for t, _ in out["shortlists"]] == [2, 5, 8]          # t = tau_s + m * tau_r
+    assert len(out["overlap"]) == 2 and len(out["loss"]) == steps
+    nbatch = Z.shape[0] // B
+    for t in range(steps):
+        neg = out["neg"][t]
+        lo = (t % nbatch) * B
+        if t < tau_s:
+            # warm-up: no hard slots; the first k_h ids are uniform draws, not a shortlist row
+            assert neg.shape == (B, k_h + k_r)
+        else:
+            last = [sl for tt, sl in out["shortlists"] if tt <= t][-1]   # the newest refresh not after t
+            assert (neg[:, :k_h] == last[lo:lo + B]).all()                # hard negatives are that (stale) list
+            for i in range(B):
+                assert not set(neg[i, k_h:].tolist()) & set(last[lo + i].tolist())
+    # the first refresh is the exact search on the matrix as it stood after the warm-up steps:
+    # replay those steps by hand with the warm-up sampler
+    W2 = W.copy()
+    for t in range(tau_s):
+        lo = (t % nbatch) * B
+        neg, logq = orc.sample_negatives(None, B, k_h, k_r, W.shape[0], 100 + t)
+        assert (neg == out["neg"][t]).all()
+        r = orc.xc_step(Z[lo:lo + B], W2, pos[lo:lo + B], neg, logq, 0.5)
+        W2[r["touched"]] = r["W_rows"]
+    brute = np.argsort(-(Z @ W2.T), axis=1, kind="stable")[:, :k_h]
+    assert (np.sort(brute, axis=1) == np.sort(out["shortlists"][0][1], axis=1)).all()
+
+
+def test_schedule_with_zero_learning_rate_is_stationary():
+    W, Z, pos = _schedule_inputs(seed=5)
+    B, k_h, k_r, steps = 4, 3, 5, 10
+    nbatch = Z.shape[0] // B                      # 3 batches
+    seeds = [7 + (t % nbatch) for t in range(steps)]         # same seed whenever the same batch returns
+    W0 = W.copy()
+    out = orc.train_schedule(Z, W, pos, B, k_h, k_r, steps, 0, 2, 0.0, seeds)
+    assert (W == W0).all()
+    assert out["overlap"] == [1.0] * (len(out["shortlists"]) - 1)       # nothing moved between refreshes
+    for t in range(nbatch, steps):
+        assert out["loss"][t] == out["loss"][t - nbatch]                # batches cycle through the pool
+    assert len(set(round(x, 12) for x in out["loss"][:nbatch])) == nbatch   # ... and differ from each other
