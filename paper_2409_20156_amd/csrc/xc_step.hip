@@ -605,8 +605,14 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
 
 // ---------------------------------------------------------------------------
 // per touched label: dW = sum over its pairs of g * z_i ; w <- w - lr * dW
-// One group of G lanes per segment, chunks distributed as in gather_kernel.
+// One group of G lanes per segment, chunks distributed as in gather_kernel.  A label shared by
+// more than kLongSeg pairs (a frequent positive, a hard negative of many queries) would make
+// its group the last to finish: such segments are queued and afterwards worked on by the whole
+// workgroup, group g taking pairs g, g + NG, ... and the partial sums added in group order.
 // ---------------------------------------------------------------------------
+constexpr int kLongSeg = 16;        // pairs above which a segment is shared by the workgroup
+constexpr int kMaxLong = 32;        // queued long segments per workgroup (more are done in place)
+
 template <typename T, int CPL>
 __global__ __launch_bounds__(kStepThreads)
 void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n_magic, int n_shift, int G,
@@ -617,7 +623,12 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
                    const float* __restrict__ dz_part, int SQ, int64_t BD, float* __restrict__ dZ) {
     constexpr int EPC = Elem<T>::kPerChunk;
     constexpr int U = 2;
+    extern __shared__ float lpart[];              // [NG][CPL][G][EPC] partial sums of a long segment
+    __shared__ int long_q[kMaxLong];
+    __shared__ int n_long;
     const int tid = threadIdx.x;
+    if (tid == 0) n_long = 0;
+    __syncthreads();
     // dZ = sum of the partials written by the workgroups that shared a query, in split order
     // (independent of the row updates below; done here because this grid is large)
     if (SQ > 1) {
@@ -641,11 +652,6 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
     int p0_n = 0, p1_n = 0, label_n = 0;
     uint32_t idx0_n = 0;
     if (s < n_seg) { p0_n = seg_start[s]; p1_n = seg_start[s + 1]; label_n = touched[s]; idx0_n = seg_idx0[s]; }
-    for (; s < n_seg; s += s_step) {
-    const int p0 = p0_n, p1 = p1_n;
-    const int64_t label = label_n;
-    const uint32_t idx0 = idx0_n;
-
     // pair index -> query row: exact division by n through a multiply-high (n_magic, n_shift
     // from the host; valid for every index below 2^31)
     auto query_of = [&](uint32_t idx) -> int64_t {
@@ -653,6 +659,24 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
         const uint32_t t = __umulhi(idx, n_magic);
         return static_cast<int64_t>((t + ((idx - t) >> 1)) >> n_shift);
     };
+    for (; s < n_seg; s += s_step) {
+    const int p0 = p0_n, p1 = p1_n;
+    const int64_t label = label_n;
+    const uint32_t idx0 = idx0_n;
+    const int64_t s_cur = s;
+    if (s + s_step < n_seg) {
+        const int64_t sn = s + s_step;
+        p0_n = seg_start[sn]; p1_n = seg_start[sn + 1]; label_n = touched[sn]; idx0_n = seg_idx0[sn];
+    }
+    if (p1 - p0 > kLongSeg) {                     // uniform within the group
+        int slot = 0;
+        if (gl == 0) slot = atomicAdd(&n_long, 1);
+        slot = __shfl(slot, 0, G);
+        if (slot < kMaxLong) {
+            if (gl == 0) long_q[slot] = static_cast<int>(s_cur);
+            continue;
+        }
+    }
 
     // hop 2: the row of W, the coefficient and the query row of the first pair, together
     unsigned char* wrow = reinterpret_cast<unsigned char*>(W) + label * row_bytes;
@@ -672,11 +696,6 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
         }
     }
 
-    if (s + s_step < n_seg) {
-        const int64_t sn = s + s_step;
-        p0_n = seg_start[sn]; p1_n = seg_start[sn + 1]; label_n = touched[sn]; idx0_n = seg_idx0[sn];
-    }
-
     float acc[CPL][EPC];
 #pragma unroll
     for (int j = 0; j < CPL; ++j) {
@@ -686,35 +705,44 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
         for (int e = 0; e < EPC; ++e) acc[j][e] = g0 * zf[e];
     }
 
-    // further pairs of the same label, in sorted (= original) order
-    for (int p = p0 + 1; p < p1; p += U) {
-        float g[U];
-        uint32_t idx[U];
-        uint4 rz[U][CPL];
+    // further pairs of the same label, in sorted (= original) order.  A round first fetches the
+    // pair index, coefficient and query row of up to G pairs, one per lane of the group, so that a
+    // long segment (a label many queries share) pays the two dependent index loads once per G
+    // pairs; the rows then follow U at a time.
+    for (int pb = p0 + 1; pb < p1; pb += G) {
+        const int nb = (p1 - pb) < G ? (p1 - pb) : G;
+        float my_g = 0.0f;
+        int64_t my_q = 0;
+        if (gl < nb) {
+            const uint32_t idx = vals[pb + gl];
+            my_g = gco[idx];
+            my_q = query_of(idx);
+        }
+        for (int u0 = 0; u0 < nb; u0 += U) {
+            float g[U];
+            uint4 rz[U][CPL];
 #pragma unroll
-        for (int u = 0; u < U; ++u) idx[u] = p + u < p1 ? vals[p + u] : 0u;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (p + u < p1) {
-                g[u] = gco[idx[u]];
-                const int64_t qi = query_of(idx[u]);
+            for (int u = 0; u < U; ++u) {
+                g[u] = __shfl(my_g, u0 + u, G);          // lanes past nb hold 0 and row 0: harmless
+                const int64_t qi = __shfl(my_q, u0 + u, G);
 #pragma unroll
                 for (int j = 0; j < CPL; ++j) {
                     const int ch = gl + j * G;
                     rz[u][j] = make_uint4(0, 0, 0, 0);
-                    if (ch < nchunks) rz[u][j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
+                    if (ch < nchunks && u0 + u < nb)
+                        rz[u][j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
                 }
             }
-        }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (p + u < p1) {
+            for (int u = 0; u < U; ++u) {
+                if (u0 + u < nb) {
 #pragma unroll
-                for (int j = 0; j < CPL; ++j) {
-                    float zf[EPC];
-                    Elem<T>::unpack(rz[u][j], zf);
+                    for (int j = 0; j < CPL; ++j) {
+                        float zf[EPC];
+                        Elem<T>::unpack(rz[u][j], zf);
 #pragma unroll
-                    for (int e = 0; e < EPC; ++e) acc[j][e] = fmaf(g[u], zf[e], acc[j][e]);
+                        for (int e = 0; e < EPC; ++e) acc[j][e] = fmaf(g[u], zf[e], acc[j][e]);
+                    }
                 }
             }
         }
@@ -734,6 +762,92 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
         }
     }
     }   // segments of this group
+
+    // ---- queued long segments: the whole workgroup on each
+    __syncthreads();
+    const int nl = n_long < kMaxLong ? n_long : kMaxLong;
+    const int grp = tid / G;
+    for (int li = 0; li < nl; ++li) {
+        const int64_t sl = long_q[li];
+        const int p0 = seg_start[sl], p1 = seg_start[sl + 1];
+        const int64_t label = touched[sl];
+        float acc[CPL][EPC];
+#pragma unroll
+        for (int j = 0; j < CPL; ++j)
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) acc[j][e] = 0.0f;
+        // this group's pairs are p0 + grp + NG * m; a round fetches the metadata of G of them
+        for (int m0 = 0; p0 + grp + NG * m0 < p1; m0 += G) {
+            const int pm = p0 + grp + NG * (m0 + gl);
+            float my_g = 0.0f;
+            int64_t my_q = 0;
+            if (pm < p1) {
+                const uint32_t idx = vals[pm];
+                my_g = gco[idx];
+                my_q = query_of(idx);
+            }
+            const int left = (p1 - (p0 + grp + NG * m0) + NG - 1) / NG;      // pairs of this group from m0 on
+            const int nb = left < G ? left : G;
+            for (int u0 = 0; u0 < nb; u0 += U) {
+                float g[U];
+                uint4 rz[U][CPL];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    g[u] = __shfl(my_g, u0 + u, G);
+                    const int64_t qi = __shfl(my_q, u0 + u, G);
+#pragma unroll
+                    for (int j = 0; j < CPL; ++j) {
+                        const int ch = gl + j * G;
+                        rz[u][j] = make_uint4(0, 0, 0, 0);
+                        if (ch < nchunks && u0 + u < nb)
+                            rz[u][j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (u0 + u < nb) {
+#pragma unroll
+                        for (int j = 0; j < CPL; ++j) {
+                            float zf[EPC];
+                            Elem<T>::unpack(rz[u][j], zf);
+#pragma unroll
+                            for (int e = 0; e < EPC; ++e) acc[j][e] = fmaf(g[u], zf[e], acc[j][e]);
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < CPL; ++j)
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) lpart[((grp * CPL + j) * G + gl) * EPC + e] = acc[j][e];
+        __syncthreads();
+        if (grp == li % NG) {                      // one group adds the partial sums in group order
+            unsigned char* wrow = reinterpret_cast<unsigned char*>(W) + label * row_bytes;
+            unsigned char* orow = rows_out ? reinterpret_cast<unsigned char*>(rows_out) + sl * row_bytes : nullptr;
+#pragma unroll
+            for (int j = 0; j < CPL; ++j) {
+                const int ch = gl + j * G;
+                if (ch < nchunks) {
+                    const uint4 wv = *reinterpret_cast<const uint4*>(wrow + ch * 16);
+                    float tot[EPC];
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) tot[e] = lpart[((0 * CPL + j) * G + gl) * EPC + e];
+                    for (int g2 = 1; g2 < NG; ++g2)
+#pragma unroll
+                        for (int e = 0; e < EPC; ++e) tot[e] += lpart[((g2 * CPL + j) * G + gl) * EPC + e];
+                    float wf[EPC];
+                    Elem<T>::unpack(wv, wf);
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) wf[e] = fmaf(-lr, tot[e], wf[e]);
+                    const uint4 o = Elem<T>::pack(wf);
+                    *reinterpret_cast<uint4*>(wrow + ch * 16) = o;
+                    if (orow) *reinterpret_cast<uint4*>(orow + ch * 16) = o;
+                }
+            }
+        }
+        __syncthreads();
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -846,7 +960,8 @@ static void launch_update(const StepPlan& pl, hipStream_t st, const void* Z, voi
     if (nwg > kUpdateMaxGrid) nwg = kUpdateMaxGrid;
     const dim3 grid(static_cast<unsigned>(nwg));
 #define XC_UPDATE(CPL)                                                                            \
-    XC_LAUNCH(K_UPDATE, st, (update_kernel<T, CPL><<<grid, kStepThreads, 0, st>>>(                \
+    XC_LAUNCH(K_UPDATE, st, (update_kernel<T, CPL><<<grid, kStepThreads,                          \
+        kStepThreads * CPL * Elem<T>::kPerChunk * sizeof(float), st>>>(                             \
         static_cast<const T*>(Z), static_cast<T*>(W), d, pl.n_magic, pl.n_shift, pl.G, vals, gco, touched, seg_start, \
         seg_idx0, n_touched, lr, static_cast<T*>(rows_out), dz_part, SQ, BD, dZ)))
     switch (pl.cpl) {

@@ -116,3 +116,20 @@ def test_step_is_bitwise_reproducible():
         res.append((out["loss"].cpu(), out["dZ"].cpu(), Wg.cpu()))
     assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
     assert torch.equal(res[0][2].view(torch.int16), res[1][2].view(torch.int16))
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_step_many_long_segments(dtype):
+    """Every label is shared by 17 pairs (more than a lane group takes alone) and there are enough
+    such labels that some workgroups exceed their queue of shared segments: both the cooperative
+    path and the in-place path of the row update are exercised."""
+    B, L, d, k_p, n = 1088, 90000, 64, 1, 1280            # 64 blocks of 17 queries with the same negatives
+    Z = synth.make_matrix(8, synth.TAG_Z, B, d, dtype, "cuda:0")
+    W = synth.make_matrix(8, synth.TAG_W, L, d, dtype, "cuda:0")
+    blk = np.arange(B) // 17
+    neg = (blk[:, None] * n + np.arange(n)[None, :]).astype(np.int32)          # < 64 * 1280 = 81920
+    pos = (81920 + np.arange(B) % 5000).astype(np.int32).reshape(B, 1)         # positives elsewhere
+    logq = np.full((B, n), np.log(0.5), dtype=np.float32)
+    out, ref = _run_and_check(Z, W, pos, neg, logq, f64(Z), f64(W), 0.05 if dtype == torch.bfloat16 else 0.3,
+                              orc.LOSS_BCE)
+    assert len(ref["touched"]) == 64 * n + B
