@@ -645,13 +645,6 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
     const int64_t row_bytes = static_cast<int64_t>(d) * sizeof(T);
     const unsigned char* Zb = reinterpret_cast<const unsigned char*>(Z);
     const int64_t n_seg = n_touched[0];
-    // a group walks several segments so that waves live long enough to keep the chip full;
-    // hop 1 (everything that identifies a segment) is fetched one segment ahead
-    const int64_t s_step = static_cast<int64_t>(gridDim.x) * NG;
-    int64_t s = static_cast<int64_t>(blockIdx.x) * NG + tid / G;
-    int p0_n = 0, p1_n = 0, label_n = 0;
-    uint32_t idx0_n = 0;
-    if (s < n_seg) { p0_n = seg_start[s]; p1_n = seg_start[s + 1]; label_n = touched[s]; idx0_n = seg_idx0[s]; }
     // pair index -> query row: exact division by n through a multiply-high (n_magic, n_shift
     // from the host; valid for every index below 2^31)
     auto query_of = [&](uint32_t idx) -> int64_t {
@@ -659,15 +652,47 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
         const uint32_t t = __umulhi(idx, n_magic);
         return static_cast<int64_t>((t + ((idx - t) >> 1)) >> n_shift);
     };
+    // A group walks several segments so that waves live long enough to keep the chip full.  The
+    // loads run ahead of the arithmetic: hop 1 (what identifies a segment) two segments ahead,
+    // hop 2 (the row of W, the coefficient and the query row of the first pair) one ahead.
+    struct Hop1 { int p0, p1, label; uint32_t idx0; };
+    auto load_hop1 = [&](int64_t sx, Hop1& h) {
+        h.p0 = seg_start[sx]; h.p1 = seg_start[sx + 1]; h.label = touched[sx]; h.idx0 = seg_idx0[sx];
+    };
+    auto load_hop2 = [&](const Hop1& h, uint4 (&wv)[CPL], uint4 (&z0)[CPL], float& g0) {
+        const unsigned char* wr = reinterpret_cast<const unsigned char*>(W) + static_cast<int64_t>(h.label) * row_bytes;
+        g0 = gco[h.idx0];
+        const int64_t qi = query_of(h.idx0);
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const int ch = gl + j * G;
+            wv[j] = make_uint4(0, 0, 0, 0);
+            z0[j] = make_uint4(0, 0, 0, 0);
+            if (ch < nchunks) {
+                wv[j] = *reinterpret_cast<const uint4*>(wr + ch * 16);
+                z0[j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
+            }
+        }
+    };
+    const int64_t s_step = static_cast<int64_t>(gridDim.x) * NG;
+    int64_t s = static_cast<int64_t>(blockIdx.x) * NG + tid / G;
+    Hop1 h_n = {0, 0, 0, 0u}, h_nn = {0, 0, 0, 0u};
+    uint4 wv_n[CPL], z0_n[CPL];
+    float g0_n = 0.0f;
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) { wv_n[j] = make_uint4(0, 0, 0, 0); z0_n[j] = make_uint4(0, 0, 0, 0); }
+    if (s < n_seg) { load_hop1(s, h_n); load_hop2(h_n, wv_n, z0_n, g0_n); }
+    if (s + s_step < n_seg) load_hop1(s + s_step, h_nn);
     for (; s < n_seg; s += s_step) {
-    const int p0 = p0_n, p1 = p1_n;
-    const int64_t label = label_n;
-    const uint32_t idx0 = idx0_n;
+    const int p0 = h_n.p0, p1 = h_n.p1;
+    const int64_t label = h_n.label;
+    const float g0 = g0_n;
+    uint4 wv[CPL], z0[CPL];
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) { wv[j] = wv_n[j]; z0[j] = z0_n[j]; }
     const int64_t s_cur = s;
-    if (s + s_step < n_seg) {
-        const int64_t sn = s + s_step;
-        p0_n = seg_start[sn]; p1_n = seg_start[sn + 1]; label_n = touched[sn]; idx0_n = seg_idx0[sn];
-    }
+    if (s + s_step < n_seg) { h_n = h_nn; load_hop2(h_n, wv_n, z0_n, g0_n); }
+    if (s + 2 * s_step < n_seg) load_hop1(s + 2 * s_step, h_nn);
     if (p1 - p0 > kLongSeg) {                     // uniform within the group
         int slot = 0;
         if (gl == 0) slot = atomicAdd(&n_long, 1);
@@ -677,24 +702,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
             continue;
         }
     }
-
-    // hop 2: the row of W, the coefficient and the query row of the first pair, together
     unsigned char* wrow = reinterpret_cast<unsigned char*>(W) + label * row_bytes;
-    uint4 wv[CPL], z0[CPL];
-    const float g0 = gco[idx0];
-    {
-        const int64_t qi = query_of(idx0);
-#pragma unroll
-        for (int j = 0; j < CPL; ++j) {
-            const int ch = gl + j * G;
-            wv[j] = make_uint4(0, 0, 0, 0);
-            z0[j] = make_uint4(0, 0, 0, 0);
-            if (ch < nchunks) {
-                wv[j] = *reinterpret_cast<const uint4*>(wrow + ch * 16);
-                z0[j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
-            }
-        }
-    }
 
     float acc[CPL][EPC];
 #pragma unroll
