@@ -63,9 +63,19 @@ __device__ __noinline__ float wave_select_k(uint64_t* __restrict__ buf, Load loa
         valid[r] = idx < n;
         key[r] = valid[r] ? load(idx) : kKeySentinel;
     }
-    uint64_t prefix = 0, pmask = 0;
+    // leading bytes shared by every key (scores of one query lie close together) need no pass:
+    // all keys would fall into one histogram bin, one atomic after the other
+    uint64_t diff = 0;
+    const uint64_t ref = __shfl(key[0], 0, kWave);          // index 0 is valid (n > k >= 1)
+#pragma unroll
+    for (int r = 0; r < R; ++r) diff |= valid[r] ? (key[r] ^ ref) : 0ull;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) diff |= __shfl_xor(diff, off, kWave);
+    const int first_pass = diff == 0ull ? 8 : (__clzll(static_cast<long long>(diff)) >> 3);
+    uint64_t pmask = first_pass == 0 ? 0ull : (~0ull << (64 - 8 * first_pass));
+    uint64_t prefix = ref & pmask;
     int need = k;
-    for (int pass = 0; pass < 8; ++pass) {
+    for (int pass = first_pass; pass < 8; ++pass) {
         const int shift = 56 - 8 * pass;
 #pragma unroll
         for (int j = 0; j < 4; ++j) hist[lane * 4 + j] = 0;
@@ -565,9 +575,10 @@ void mine_select_kernel(uint64_t* __restrict__ glist, int32_t* __restrict__ gcnt
     int n = gcnt[q];
     n = n < glist_cap ? n : glist_cap;
     if (n > k) {
-        const float t = (n <= kSelectRegs * kWave)
-                            ? wave_select_k<kSelectRegs>(list, [list](int idx) { return list[idx]; }, n, k, hist[wave])
-                            : wave_select_stream(list, n, k, hist[wave]);
+        auto at = [list](int idx) { return list[idx]; };
+        const float t = (n <= kSelectRegs / 2 * kWave) ? wave_select_k<kSelectRegs / 2>(list, at, n, k, hist[wave])
+                        : (n <= kSelectRegs * kWave)   ? wave_select_k<kSelectRegs>(list, at, n, k, hist[wave])
+                                                       : wave_select_stream(list, n, k, hist[wave]);
         n = k;
         if (lane == 0) { gcnt[q] = k; tau_g[q] = float_to_ordered(t); }
     }

@@ -3,7 +3,7 @@
 // Sec. 4).  Three kernel groups:
 //   gather_kernel   per query: gather the candidate rows of W, scores, loss,
 //                   d loss/d score per pair, dZ -- one pass over the rows
-//   radix sort      (label, pair index) by label, stable, 8 bits per pass
+//   radix sort      (label, pair index) by label, stable, digits of up to 11 bits
 //   heads + update  segment heads -> touched list; per touched label the summed
 //                   gradient over its pairs and the fused SGD row update
 #include "xc_common.h"

@@ -93,3 +93,22 @@ def test_mine_is_reproducible_run_to_run():
     a = _run(Z, W, 64)
     b = _run(Z, W, 64)
     assert (a[0] == b[0]).all() and (a[1] == b[1]).all()
+
+
+def test_inference_topk_precision_on_planted_positives():
+    """The same search serves prediction (top-5 labels of a query): queries are noisy copies of
+    their label's row, precision@k of the GPU result equals the oracle's and is high."""
+    dev = "cuda:0"
+    L, d, Zq, k = 50000, 256, 400, 5
+    W = synth.make_matrix(4, synth.TAG_W, L, d, torch.bfloat16, dev)
+    noise = synth.make_matrix(4, synth.TAG_Z, Zq, d, torch.bfloat16, dev)
+    truth = (np.arange(Zq) * 97 + 3) % L
+    Z = (W[torch.as_tensor(truth, device=dev)].float() + 0.8 * noise.float()).to(torch.bfloat16)
+    ids, sc = _run(Z, W, k)
+    Z64, W64 = f64(Z), f64(W)
+    ids_o, sc_o = orc.mine_negatives(Z64, W64, k)
+    check_topk(ids, sc, ids_o, sc_o, Z64, W64)
+    p1 = float((ids[:, 0] == truth).mean())
+    p5 = float((ids == truth[:, None]).any(axis=1).mean())
+    assert p1 == float((ids_o[:, 0] == truth).mean()) and p5 == float((ids_o == truth[:, None]).any(axis=1).mean())
+    assert p1 > 0.9 and p5 >= p1
