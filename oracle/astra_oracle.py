@@ -284,31 +284,41 @@ def xc_step(Z, W, pos, neg, logq, lr: float, kind: int = LOSS_BCE,
 # full-label references (tiny inputs only, O(B L d))
 # --------------------------------------------------------------------------
 def train_schedule(Z_pool, W, pos_pool, B: int, k_h: int, k_r: int, steps: int, tau_s: int, tau_r: int,
-                   lr: float, seeds, kind: int = LOSS_BCE, storage: str = "f32"):
+                   lr: float, seeds, kind: int = LOSS_BCE, storage: str = "f32", lag: int = 0):
     """Alg. 1 for the classifier alone (encoder frozen: the query pool Z_pool is fixed).
 
     Step t uses the mini-batch of rows (t mod nbatch)*B .. +B of the pool.  While t < tau_s the
     negatives are all uniform (warm-up).  From t = tau_s on, the shortlists of the WHOLE pool are
-    rebuilt by exact search with the current W whenever (t - tau_s) is a multiple of tau_r, and
-    the step takes its batch's rows of the (possibly stale) shortlist as hard negatives plus k_r
-    uniform ones.  seeds[t] is the sampler's seed of step t.  W (float64 [L,d]) is updated in
-    place, rounded to `storage` after every step as the stored matrix is.
+    rebuilt by exact search whenever (t - tau_s) is a multiple of tau_r, from W as it stands
+    before step t.  With lag = 0 step t already uses them; with lag > 0 the search is taken to
+    run beside the training steps (the paper's asynchronous refresh) and its result replaces the
+    older shortlists only from step t + lag on, so steps t .. t+lag-1 still use the older ones
+    (warm-up negatives if there are none yet).  The step takes its batch's rows of the active
+    (stale) shortlist as hard negatives plus k_r uniform ones.  seeds[t] is the sampler's seed of
+    step t.  W (float64 [L,d]) is updated in place, rounded to `storage` after every step as the
+    stored matrix is.
 
-    Returns a dict: loss (list, per step), neg (list, per step: the sampled ids), shortlists (list of (t, int32 [pool,k_h]) per refresh),
-    overlap (list, per refresh after the first: mean over queries of |fresh & stale| / k_h).
+    Returns a dict: loss (list, per step), neg (list, per step: the sampled ids), shortlists
+    (list of (t, int32 [pool,k_h]) per refresh, t = the step whose W was searched), overlap
+    (list, per refresh after the first: mean over queries of |fresh & previous| / k_h).
     """
     pool, L = Z_pool.shape[0], W.shape[0]
     nbatch = max(1, pool // B)
     out = {"loss": [], "shortlists": [], "overlap": [], "neg": []}
-    shortlist = None
+    shortlist = None          # active
+    newest = None             # last one built (equal to the active one once its lag has passed)
+    pending = []              # (activation step, shortlist)
     for t in range(steps):
         if t >= tau_s and (t - tau_s) % tau_r == 0:
             fresh, _ = mine_negatives(Z_pool, W, k_h)
-            if shortlist is not None:
-                same = [len(set(fresh[q].tolist()) & set(shortlist[q].tolist())) for q in range(pool)]
+            if newest is not None:
+                same = [len(set(fresh[q].tolist()) & set(newest[q].tolist())) for q in range(pool)]
                 out["overlap"].append(float(np.mean(same)) / k_h)
-            shortlist = fresh
+            newest = fresh
+            pending.append((t + lag, fresh))
             out["shortlists"].append((t, fresh.copy()))
+        while pending and pending[0][0] <= t:
+            shortlist = pending.pop(0)[1]
         b = t % nbatch
         lo, hi = b * B, (b + 1) * B
         rows = shortlist[lo:hi] if shortlist is not None else None

@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--taus", default="1,5,20,100")
+    ap.add_argument("--lag", type=int, default=0, help="steps a refresh runs beside the training steps before it takes over (0 = synchronous)")
     args = ap.parse_args()
     dev = "cuda:0"
     wl = synth.WORKLOADS[args.workload]
@@ -47,7 +48,7 @@ def main():
     for tau in [int(x) for x in args.taus.split(",")]:
         # timed run
         W, Z, pos = _job(wl, dev)
-        sch = Schedule(Z, W, pos, wl.B, wl.k_h, wl.k_r, 0, tau, wl.lr)
+        sch = Schedule(Z, W, pos, wl.B, wl.k_h, wl.k_r, 0, tau, wl.lr, lag=min(args.lag, tau))
         sch.step(seeds[0])                                   # first refresh and step: warm-up, untimed
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -57,17 +58,18 @@ def main():
         el = time.perf_counter() - t0
         # overlap run (same trajectory: everything is deterministic)
         W, Z, pos = _job(wl, dev)
-        sch = Schedule(Z, W, pos, wl.B, wl.k_h, wl.k_r, 0, tau, wl.lr)
+        sch = Schedule(Z, W, pos, wl.B, wl.k_h, wl.k_r, 0, tau, wl.lr, lag=min(args.lag, tau))
         overlaps = []
         for t in range(args.steps):
             sch.step(seeds[t])
             if sch.refreshed:
-                pair = sch.stale_and_fresh()
+                pair = sch.previous_and_fresh()
                 if pair is not None:
+                    torch.cuda.synchronize()
                     overlaps.append(_overlap(*pair))
         torch.cuda.synchronize()
         n = args.steps - 1
-        print(json.dumps({"workload": wl.name, "tau_r": tau, "steps": args.steps,
+        print(json.dumps({"workload": wl.name, "tau_r": tau, "lag": min(args.lag, tau), "steps": args.steps,
                           "refreshes_timed": sum(1 for t in range(1, args.steps) if t % tau == 0),
                           "steps_per_s": n / el, "queries_per_s": n * wl.B / el,
                           "mean_overlap_fresh_vs_stale": sum(overlaps) / len(overlaps) if overlaps else None,

@@ -4,6 +4,12 @@ Argument marshalling and the step counter only: warm-up steps with uniform negat
 t < tau_s, then a refresh of the whole pool's shortlists every tau_r steps (xc_mine_negatives
 with the current W) and hard + random steps (xc_sample_negatives, xc_step).  All buffers are
 allocated once, before the first step.
+
+With lag > 0 the refresh is asynchronous, as in the paper's pipeline: at a refresh step the
+current W is copied to a snapshot, the search runs on a second stream (default priority) over
+that snapshot while the training steps go on with the older shortlists, and the new shortlists
+take over exactly `lag` steps later (the step stream waits for the search there), so the result
+does not depend on timing.
 """
 from __future__ import annotations
 
@@ -14,9 +20,12 @@ from . import binding as xc
 
 class Schedule:
     def __init__(self, Z_pool: torch.Tensor, W: torch.Tensor, pos_pool: torch.Tensor, B: int, k_h: int,
-                 k_r: int, tau_s: int, tau_r: int, lr: float, kind: int = xc.XC_LOSS_BCE):
+                 k_r: int, tau_s: int, tau_r: int, lr: float, kind: int = xc.XC_LOSS_BCE, lag: int = 0):
+        if lag < 0 or (lag > 0 and lag > tau_r):
+            raise ValueError("lag must lie in [0, tau_r]")
         self.Z, self.W, self.pos = Z_pool, W, pos_pool
         self.B, self.k_h, self.k_r, self.tau_s, self.tau_r, self.lr, self.kind = B, k_h, k_r, tau_s, tau_r, lr, kind
+        self.lag = lag
         dev = W.device
         pool, d = Z_pool.shape
         L = W.shape[0]
@@ -28,7 +37,9 @@ class Schedule:
         self.mine_ws = torch.empty(xc.mine_workspace(pool, L, d, k_h, code), dtype=torch.uint8, device=dev)
         self.step_ws = torch.empty(xc.step_workspace(B, d, k_p, n_neg, code), dtype=torch.uint8, device=dev)
         self.shortlist = [torch.empty((pool, k_h), dtype=torch.int32, device=dev) for _ in range(2)]
-        self.cur = -1                                  # index of the valid shortlist buffer, -1 = none yet
+        self.cur = -1                                  # index of the active shortlist buffer, -1 = none yet
+        self.built = -1                                # index of the newest built (or being built) buffer
+        self.pending = None                            # (activation step, buffer index, event) of a running search
         self.neg = torch.empty((B, n_neg), dtype=torch.int32, device=dev)
         self.logq = torch.empty((B, n_neg), dtype=torch.float32, device=dev)
         P = B * (k_p + n_neg)
@@ -36,25 +47,47 @@ class Schedule:
                     "dZ": torch.empty((B, d), dtype=torch.float32, device=dev),
                     "touched": torch.empty(P, dtype=torch.int32, device=dev),
                     "n_touched": torch.empty(1, dtype=torch.int32, device=dev)}
+        if lag > 0:
+            self.W_snap = torch.empty_like(W)
+            self.side = torch.cuda.Stream(device=dev)              # default priority
         self.t = 0
-        self.refreshed = False                         # the last step() call rebuilt the shortlists
+        self.refreshed = False                         # the last step() call started (lag>0) or did a refresh
+        self.had_previous = False
 
-    def stale_and_fresh(self):
-        """(previous, current) shortlist tensors after a refresh that had a predecessor, else None."""
-        if self.cur < 0 or not self.had_previous:
+    def previous_and_fresh(self):
+        """(previous, newest) shortlist tensors after a refresh that had a predecessor, else None.
+        With lag > 0 the caller must synchronise before reading the newest one."""
+        if self.built < 0 or not self.had_previous:
             return None
-        return self.shortlist[1 - self.cur], self.shortlist[self.cur]
+        return self.shortlist[1 - self.built], self.shortlist[self.built]
 
-    had_previous = False
+    stale_and_fresh = previous_and_fresh
 
     def step(self, seed: int):
         t = self.t
         self.refreshed = False
+        main = torch.cuda.current_stream()
+        if self.pending is not None and self.pending[0] <= t:
+            main.wait_event(self.pending[2])           # the search has to be finished from here on
+            self.cur = self.pending[1]                 # (also before its snapshot and workspace are reused)
+            self.pending = None
         if t >= self.tau_s and (t - self.tau_s) % self.tau_r == 0:
-            nxt = 0 if self.cur < 0 else 1 - self.cur
-            xc.mine_negatives(self.Z, self.W, self.k_h, workspace=self.mine_ws, out=self.shortlist[nxt])
-            self.had_previous = self.cur >= 0
-            self.cur = nxt
+            nxt = 0 if self.built < 0 else 1 - self.built
+            self.had_previous = self.built >= 0
+            if self.lag == 0:
+                xc.mine_negatives(self.Z, self.W, self.k_h, workspace=self.mine_ws, out=self.shortlist[nxt])
+                self.cur = nxt
+            else:
+                self.W_snap.copy_(self.W)                                      # on the step stream
+                snap_done = torch.cuda.Event()
+                snap_done.record(main)
+                done = torch.cuda.Event()
+                with torch.cuda.stream(self.side):
+                    self.side.wait_event(snap_done)
+                    xc.mine_negatives(self.Z, self.W_snap, self.k_h, workspace=self.mine_ws, out=self.shortlist[nxt])
+                    done.record(self.side)
+                self.pending = (t + self.lag, nxt, done)
+            self.built = nxt
             self.refreshed = True
         b = t % self.nbatch
         lo, hi = b * self.B, (b + 1) * self.B

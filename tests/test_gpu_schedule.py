@@ -1,4 +1,5 @@
-"""GPU parity of the outer loop of Alg. 1 (warm-up, periodic refresh, hard + random steps):
+"""GPU parity of the outer loop of Alg. 1 (warm-up, periodic refresh, synchronous or
+running beside the steps with a fixed lag, hard + random steps):
 the library driven by paper_2409_20156_amd.schedule against the oracle's train_schedule, each on
 its own copy of the same generated inputs (no state is copied between the two)."""
 import numpy as np
@@ -13,8 +14,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("kind", [orc.LOSS_BCE, orc.LOSS_SOFTMAX])
-def test_schedule_matches_oracle(kind):
+@pytest.mark.parametrize("kind,lag", [(orc.LOSS_BCE, 0), (orc.LOSS_SOFTMAX, 0), (orc.LOSS_BCE, 2), (orc.LOSS_BCE, 1)])
+def test_schedule_matches_oracle(kind, lag):
     from paper_2409_20156_amd.schedule import Schedule
     L, d, B, pool, k_p, k_h, k_r = 4096, 64, 32, 64, 2, 8, 16
     steps, tau_s, tau_r, lr = 7, 1, 2, 0.3
@@ -24,9 +25,10 @@ def test_schedule_matches_oracle(kind):
     Z = synth.add_positive_signal(Z, W, pos)
     seeds = [synth.step_seed(synth.BASE_SEED, 9, t) for t in range(steps)]
     W64, Z64 = f64(W), f64(Z)
-    ref = orc.train_schedule(Z64, W64, pos, B, k_h, k_r, steps, tau_s, tau_r, lr, seeds, kind=kind, storage="f32")
+    ref = orc.train_schedule(Z64, W64, pos, B, k_h, k_r, steps, tau_s, tau_r, lr, seeds, kind=kind, storage="f32",
+                             lag=lag)
 
-    sch = Schedule(Z, W, torch.tensor(pos, device=DEV), B, k_h, k_r, tau_s, tau_r, lr, kind=kind)
+    sch = Schedule(Z, W, torch.tensor(pos, device=DEV), B, k_h, k_r, tau_s, tau_r, lr, kind=kind, lag=lag)
     tol = 20 * TOL["f32"]                  # rounding differences compound over the steps
     n_ref, overlaps = 0, []
     for t in range(steps):
@@ -37,9 +39,9 @@ def test_schedule_matches_oracle(kind):
         if sch.refreshed:
             t_ref, sl_ref = ref["shortlists"][n_ref]
             assert t_ref == t
-            got = sch.shortlist[sch.cur].cpu().numpy()
+            got = sch.shortlist[sch.built].cpu().numpy()
             assert (np.sort(got, axis=1) == np.sort(sl_ref, axis=1)).all(), "refresh at step %d" % t
-            pair = sch.stale_and_fresh()
+            pair = sch.previous_and_fresh()
             if pair is not None:
                 stale, fresh = (x.cpu().numpy() for x in pair)
                 overlaps.append(np.mean([len(set(fresh[q]) & set(stale[q])) for q in range(pool)]) / k_h)

@@ -385,3 +385,27 @@ def test_schedule_with_zero_learning_rate_is_stationary():
     for t in range(nbatch, steps):
         assert out["loss"][t] == out["loss"][t - nbatch]                # batches cycle through the pool
     assert len(set(round(x, 12) for x in out["loss"][:nbatch])) == nbatch   # ... and differ from each other
+
+
+def test_schedule_lag_delays_the_takeover_of_a_refresh():
+    W, Z, pos = _schedule_inputs(seed=9)
+    B, k_h, k_r, steps, tau_s, tau_r, lag = 4, 3, 5, 9, 1, 3, 2
+    seeds = list(range(50, 50 + steps))
+    out = orc.train_schedule(Z, W.copy(), pos, B, k_h, k_r, steps, tau_s, tau_r, 0.5, seeds, lag=lag)
+    built = dict(out["shortlists"])                      # searched at steps 1, 4, 7
+    assert sorted(built) == [1, 4, 7]
+    nbatch = Z.shape[0] // B
+    for t in range(steps):
+        lo = (t % nbatch) * B
+        active = [tt for tt in built if tt + lag <= t]   # a search started at tt serves from tt + lag on
+        neg = out["neg"][t]
+        if not active:
+            # still warm-up negatives: identical to the sampler's warm-up mode for this seed
+            want, _ = orc.sample_negatives(None, B, k_h, k_r, W.shape[0], seeds[t])
+            assert (neg == want).all()
+        else:
+            assert (neg[:, :k_h] == built[max(active)][lo:lo + B]).all()
+    # the search itself used the matrix of its own step, not of the takeover step: with lag = 0
+    # the same schedule builds the same first shortlist at step 1
+    out0 = orc.train_schedule(Z, W.copy(), pos, B, k_h, k_r, 2, tau_s, tau_r, 0.5, seeds, lag=0)
+    assert (out0["shortlists"][0][1] == built[1]).all()
