@@ -11,7 +11,7 @@ static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(hipError_t e) { g_last_hip_error = static_cast<int>(e); }
 
 static const char* const kKernelNames[K_NUM_KERNELS] = {
-    "mine_tile", "mine_select", "sample", "gather", "loss_reduce", "radix_count", "radix_scan",
+    "mine_tile", "mine_select", "sample", "gather", "radix_count", "radix_scan",
     "radix_scatter", "heads_count", "heads_write", "update"};
 
 struct Pending { int id; hipEvent_t start, stop; };

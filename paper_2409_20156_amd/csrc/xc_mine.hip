@@ -22,6 +22,8 @@
 //   mine_select_kernel  after each phase, one wave per query cuts the global
 //       candidate list to its best k and publishes the new tau; after the last
 //       phase it sorts the winners by (score descending, id ascending).
+#include <mutex>
+
 #include "xc_common.h"
 
 namespace xc {
@@ -683,16 +685,24 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
     a.tau_g = tau_g;
     a.zeros = w8 + p.off_zero;
 
-    static bool attr_done = false;       // raise the dynamic LDS limit once per process
-    if (!attr_done) {
-        const void* fns[4] = {reinterpret_cast<const void*>(&mine_tile_kernel<bf16_t, false>),
-                              reinterpret_cast<const void*>(&mine_tile_kernel<bf16_t, true>),
-                              reinterpret_cast<const void*>(&mine_tile_kernel<float, false>),
-                              reinterpret_cast<const void*>(&mine_tile_kernel<float, true>)};
-        for (const void* fn : fns)
-            XC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             static_cast<int>(p.lds_tile)));
-        attr_done = true;
+    // raise the dynamic LDS limit of the tile kernels: once per device and process (the attribute
+    // belongs to the device's copy of the kernel)
+    static std::mutex attr_mu;
+    static uint64_t attr_done_mask = 0;          // bit = device ordinal (< 64)
+    {
+        int dev = 0;
+        XC_HIP_CHECK(hipGetDevice(&dev));
+        std::lock_guard<std::mutex> lock(attr_mu);
+        if (dev < 0 || dev >= 64 || !(attr_done_mask & (1ull << dev))) {
+            const void* fns[4] = {reinterpret_cast<const void*>(&mine_tile_kernel<bf16_t, false>),
+                                  reinterpret_cast<const void*>(&mine_tile_kernel<bf16_t, true>),
+                                  reinterpret_cast<const void*>(&mine_tile_kernel<float, false>),
+                                  reinterpret_cast<const void*>(&mine_tile_kernel<float, true>)};
+            for (const void* fn : fns)
+                XC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 static_cast<int>(p.lds_tile)));
+            if (dev >= 0 && dev < 64) attr_done_mask |= 1ull << dev;
+        }
     }
     const int64_t nq = p.nQT * kBN;
     mine_init_kernel<<<dim3(static_cast<unsigned>((nq + 255) / 256)), 256, 0, st>>>(tau_g, a.gcnt, nq,
