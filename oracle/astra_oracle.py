@@ -15,6 +15,12 @@ sample_negatives    Alg. 1 hard+random step and Sec. 3.1 Idea 2: all k_h stale
                     hard negatives plus k_r i.i.d. uniform draws from
                     [L] \\ H_i, p = 1/(L-k_h) as under Eq. 2.  Warm-up mode
                     (Alg. 1, t < tau_s): all negatives uniform on [L].
+sample_negatives_mixture
+                    Sec. 3.1 Idea 2 taken literally: negatives drawn from the mixture
+                    (1-r) P_imp + r P_unif, P_imp proportional to the sigmoid of the
+                    stale score over a shortlist wider than k_h (the importance
+                    sampling the paper motivates and then replaces by "retrieve the
+                    top"), r = k_r/(k_h+k_r); logq = log of the expected count.
 xc_step             Eq. 2 (sampled BCE) with its analytic gradient (form given
                     in the proof of Lemma 1) and the mini-batch SGD update of
                     W from Alg. 1; loss averaged over data points (Sec. 4).
@@ -181,6 +187,93 @@ def sample_negatives(shortlist, B: int, k_h: int, k_r: int, L: int, seed: int, r
             neg[i, first + j] = complement_select(hs, r)
         if n_draw:
             logq[i, first:] = np.float32(np.log(np.float64(n_draw) / np.float64(M)))
+    return neg, logq
+
+
+# --------------------------------------------------------------------------
+# S2'  sampling from the mixture proposal itself (Sec. 3.1, Idea 2)
+# --------------------------------------------------------------------------
+_LOG2E_Q16 = 94548                      # round(log2(e) * 2^16)
+# ln(2)^k / k! * 2^30, k = 1..5: Taylor coefficients of 2^u on [0, 1]
+_POW2_C = (744261118, 257941248, 59597083, 10327387, 1431680)
+
+
+def sigmoid_weight(score) -> int:
+    """Integer importance weight of a shortlist slot: floor-arithmetic image of
+    2^32 * sigmoid(score), the quantity the paper's importance distribution is
+    proportional to (Sec. 3.1, Observation 2).  Fixed point throughout, so that
+    the sampler is a function of the score's bits alone:
+      t = floor(clamp(score, -30, 30) * 2^16);  y = (|t| * 94548) >> 16   (|x| log2 e, Q16)
+      2^-y in Q30 from a degree-5 polynomial for the fractional part and a shift;
+      s = (E << 32) / (2^30 + E)   (sigmoid(-|x|) in Q32);  weight = s or 2^32 - s.
+    The relative accuracy (about 1e-4) only shapes the proposal: the estimator's
+    weights use the same integers, so it stays exactly unbiased.  NaN -> 0."""
+    x = np.float32(score)
+    if x != x:
+        return 0
+    x = min(max(float(x), -30.0), 30.0)
+    t = int(np.floor(np.float64(x) * 65536.0))
+    a = abs(t)
+    y = (a * _LOG2E_Q16) >> 16
+    i, f = y >> 16, y & 0xFFFF
+    if f == 0:
+        m, shift = 1 << 30, i
+    else:
+        u = 65536 - f                       # 2^-f/65536 = 2^(u/65536) / 2
+        r = _POW2_C[4]
+        for c in (_POW2_C[3], _POW2_C[2], _POW2_C[1], _POW2_C[0]):
+            r = c + ((r * u) >> 16)
+        m, shift = (1 << 30) + ((r * u) >> 16), i + 1
+    e = m >> shift if shift < 62 else 0
+    sn = (e << 32) // ((1 << 30) + e)
+    w = (1 << 32) - sn if t >= 0 else sn
+    return max(w, 1)
+
+
+def sample_negatives_mixture(shortlist, scores, B: int, M: int, k_h: int, k_r: int, L: int, seed: int, rows=None):
+    """n = k_h + k_r negatives per query, drawn independently from the mixture proposal of
+    Sec. 3.1 Idea 2 with r = k_r / n, in stratified form: slots 0..k_h-1 are draws from the
+    importance part (label of shortlist slot m with probability w_m / T, w_m =
+    sigmoid_weight(stale score of the slot), T their sum, slots with an id outside [0,L) or a
+    NaN score excluded); slots k_h.. are uniform draws from all of [0,L).  Every slot gets
+    logq = log(expected number of copies of its label among the n draws)
+         = log(k_h * W_l / T + k_r / L),  W_l = total weight of the slots holding label l,
+    so that a pair weighted by exp(-logq) makes the sampled sum an unbiased estimate of the sum
+    over all L labels (the uniform part reaches every label).  A row without any valid slot
+    falls back to n uniform draws (logq = log(n / L)), the warm-up sampler.
+    Draw j of query i uses the same 64-bit word as sample_negatives; the importance draw is
+    r = floor(u*T / 2^64) located in the running sums of the weights in slot order.
+    Returns (neg int32 [B, n], logq float32 [B, n])."""
+    n = k_h + k_r
+    neg = np.full((B, n), -1, dtype=np.int32)
+    logq = np.zeros((B, n), dtype=np.float32)
+    for i in (range(B) if rows is None else rows):
+        ids = [int(v) for v in shortlist[i][:M]]
+        w = [sigmoid_weight(scores[i][m]) if 0 <= ids[m] < L else 0 for m in range(M)]
+        T = sum(w)
+        per_label = {}
+        for m in range(M):
+            if w[m]:
+                per_label[ids[m]] = per_label.get(ids[m], 0) + w[m]
+        cum, run = [], 0
+        for m in range(M):
+            run += w[m]
+            cum.append(run)
+        n_imp = k_h if T > 0 else 0
+        for j in range(n):
+            u = draw_u64(seed, i, j)
+            if j < n_imp:
+                r = bounded(u, T)
+                m = next(mm for mm in range(M) if cum[mm] > r)
+                lab = ids[m]
+            else:
+                lab = bounded(u, L)
+            neg[i, j] = lab
+            if T > 0:
+                c = np.float64(k_h) * np.float64(per_label.get(lab, 0)) / np.float64(T) + np.float64(k_r) / np.float64(L)
+            else:
+                c = np.float64(n) / np.float64(L)
+            logq[i, j] = np.float32(np.log(c))
     return neg, logq
 
 
