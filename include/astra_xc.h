@@ -93,6 +93,30 @@ int xc_sample_negatives(const int32_t* shortlist /* [B*k_h] or NULL */, int64_t 
                         float* logq /* [B*(k_h+k_r)] out */, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Negative sampling from the mixture proposal itself (Sec. 3.1, Idea 2:
+ * P = (1-r) P_imp + r P_unif with P_imp proportional to the sigmoid of the stale score,
+ * r = k_r/(k_h+k_r)), in stratified form.  shortlist and scores are [B*M], M >= k_h wide
+ * (for example the M best labels and their scores from xc_mine_negatives).  For query i:
+ *   slots 0..k_h-1   independent draws of a shortlist slot m with probability w_m / T,
+ *                    w_m an integer image of 2^32*sigmoid(score) (about 1e-4 relative; the
+ *                    exact recipe is in the sampler's source), T the sum over the row;
+ *                    slots whose id is outside [0,L) or whose score is NaN have weight 0;
+ *   slots k_h..      independent uniform draws from all of [0,L);
+ *   logq             for every slot, log(k_h*W_l/T + k_r/L), W_l the total weight of the
+ *                    slots holding that label: the log of the expected number of copies,
+ *                    so pairs weighted by exp(-logq) estimate the sum over all L labels
+ *                    without bias.  A row without any weight: all slots uniform,
+ *                    logq = log((k_h+k_r)/L).
+ * Random words as in xc_sample_negatives (draw j of query i); the importance draw is
+ * floor(u*T/2^64) located in the running sums of the weights in slot order.  Integer
+ * arithmetic only for the ids.  Requires 1 <= M <= XC_MAX_K_SAMPLE, k_h + k_r >= 1.
+ * ------------------------------------------------------------------------- */
+int xc_sample_negatives_mixture(const int32_t* shortlist /* [B*M] */, const float* scores /* [B*M] */,
+                                int64_t B, int M, int k_h, int k_r, int64_t L, uint64_t seed,
+                                int32_t* neg /* [B*(k_h+k_r)] out */, float* logq /* [B*(k_h+k_r)] out */,
+                                void* stream);
+
+/* ---------------------------------------------------------------------------
  * One training step of the classifier layer (Alg. 1: scores on positives and
  * sampled negatives, loss of Eq. 2, SGD on W; loss averaged over the batch).
  * Per query i with score s = <z_i, w_l> on the pre-update W:

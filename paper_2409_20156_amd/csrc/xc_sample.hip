@@ -108,6 +108,129 @@ void sample_kernel(const int32_t* __restrict__ shortlist, int k_h, int k_r, int6
     }
 }
 
+// ---------------------------------------------------------------------------
+// Sampling from the mixture proposal itself (Sec. 3.1, Idea 2): k_h draws from the importance
+// part, label of shortlist slot m with probability w_m / T, and k_r uniform draws from [0, L).
+// ---------------------------------------------------------------------------
+
+// Integer image of 2^32 * sigmoid(score), fixed point throughout so that the draw is a function
+// of the score's bits: t = floor(clamp(score) * 2^16); y = |t| log2(e) in Q16; 2^-y in Q30 from
+// a degree-5 polynomial (coefficients ln(2)^k / k! * 2^30) and a shift; sigmoid(-|x|) in Q32 by
+// one integer division; mirrored for positive scores.  NaN -> 0, otherwise at least 1.
+__device__ __forceinline__ uint64_t sigmoid_weight(float score) {
+    if (score != score) return 0ull;
+    const float x = fminf(fmaxf(score, -30.0f), 30.0f);
+    const int64_t t = static_cast<int64_t>(floor(static_cast<double>(x) * 65536.0));   // exact
+    const uint64_t a = static_cast<uint64_t>(t < 0 ? -t : t);
+    const uint64_t y = (a * 94548ull) >> 16;
+    const uint64_t ip = y >> 16, f = y & 0xffffull;
+    uint64_t m = 1ull << 30;
+    uint64_t shift = ip;
+    if (f != 0) {
+        const uint64_t u = 65536ull - f;            // 2^(-f/65536) = 2^(u/65536) / 2
+        uint64_t r = 1431680ull;
+        r = 10327387ull + ((r * u) >> 16);
+        r = 59597083ull + ((r * u) >> 16);
+        r = 257941248ull + ((r * u) >> 16);
+        r = 744261118ull + ((r * u) >> 16);
+        m = (1ull << 30) + ((r * u) >> 16);
+        shift = ip + 1;
+    }
+    const uint64_t e = shift < 62 ? (m >> shift) : 0ull;
+    const uint64_t sn = (e << 32) / ((1ull << 30) + e);
+    const uint64_t w = t >= 0 ? (1ull << 32) - sn : sn;
+    return w ? w : 1ull;
+}
+
+// One workgroup per query.  LDS holds, per shortlist slot, the id, the weight, the running sum of
+// the weights in slot order (for the draw) and the slots sorted by id (for the total weight of a
+// label, which may sit in several slots).
+__global__ __launch_bounds__(kSampleThreads)
+void sample_mixture_kernel(const int32_t* __restrict__ shortlist, const float* __restrict__ scores, int M,
+                           int k_h, int k_r, int64_t L, uint64_t seed, int n2,
+                           int32_t* __restrict__ neg, float* __restrict__ logq) {
+    __shared__ int32_t ids[XC_MAX_K_SAMPLE];
+    __shared__ uint64_t wts[XC_MAX_K_SAMPLE];
+    __shared__ uint64_t cum[2][XC_MAX_K_SAMPLE];
+    __shared__ uint64_t byid[XC_MAX_K_SAMPLE];
+    const int64_t i = blockIdx.x;
+    const int n = k_h + k_r;
+    const int32_t* row = shortlist + i * M;
+    const float* srow = scores + i * M;
+    for (int m = threadIdx.x; m < n2; m += blockDim.x) {
+        int32_t id = -1;
+        uint64_t w = 0;
+        if (m < M) {
+            id = row[m];
+            if (id >= 0 && id < L) w = sigmoid_weight(srow[m]);
+        }
+        ids[m] = id;
+        wts[m] = w;
+        cum[0][m] = w;
+        byid[m] = w ? ((static_cast<uint64_t>(static_cast<uint32_t>(id)) << 32) | static_cast<uint32_t>(m)) : ~0ull;
+    }
+    __syncthreads();
+    // inclusive running sums (doubling steps between two buffers)
+    int cur = 0;
+    for (int off = 1; off < n2; off <<= 1) {
+        for (int m = threadIdx.x; m < n2; m += blockDim.x)
+            cum[cur ^ 1][m] = cum[cur][m] + (m >= off ? cum[cur][m - off] : 0ull);
+        cur ^= 1;
+        __syncthreads();
+    }
+    const uint64_t* run = cum[cur];
+    // slots ordered by label id (slots without weight last)
+    for (int size = 2; size <= n2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int t = threadIdx.x; t < n2 / 2; t += blockDim.x) {
+                const int lo = 2 * t - (t & (stride - 1));
+                const int hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const uint64_t a = byid[lo], b = byid[hi];
+                if ((a > b) == up) { byid[lo] = b; byid[hi] = a; }
+            }
+            __syncthreads();
+        }
+    }
+    const uint64_t T = run[n2 - 1];
+    const int n_imp = T > 0 ? k_h : 0;
+    const uint64_t qstate = fmix64(seed ^ (kQueryMul * static_cast<uint64_t>(i + 1)));
+    for (int j = threadIdx.x; j < n; j += blockDim.x) {
+        const uint64_t u = fmix64(qstate + kDrawMul * static_cast<uint64_t>(j + 1));
+        int64_t lab;
+        if (j < n_imp) {
+            const uint64_t r = __umul64hi(u, T);
+            int lo = 0, hi = n2 - 1;                 // first slot whose running sum exceeds r
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (run[mid] > r) hi = mid; else lo = mid + 1;
+            }
+            lab = ids[lo];
+        } else {
+            lab = static_cast<int64_t>(__umul64hi(u, static_cast<uint64_t>(L)));
+        }
+        double c;
+        if (T > 0) {
+            // total weight of the slots that hold this label
+            const uint64_t key = static_cast<uint64_t>(lab) << 32;
+            int lo = 0, hi = n2;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (byid[mid] < key) lo = mid + 1; else hi = mid;
+            }
+            uint64_t wl = 0;
+            for (int p = lo; p < n2 && (byid[p] >> 32) == static_cast<uint64_t>(lab); ++p)
+                wl += wts[static_cast<uint32_t>(byid[p])];
+            c = static_cast<double>(k_h) * static_cast<double>(wl) / static_cast<double>(T) +
+                static_cast<double>(k_r) / static_cast<double>(L);
+        } else {
+            c = static_cast<double>(n) / static_cast<double>(L);
+        }
+        neg[i * n + j] = static_cast<int32_t>(lab);
+        logq[i * n + j] = static_cast<float>(log(c));
+    }
+}
+
 }  // namespace xc
 
 extern "C" int xc_sample_negatives(const int32_t* shortlist, int64_t B, int k_h, int k_r, int64_t L,
@@ -123,6 +246,22 @@ extern "C" int xc_sample_negatives(const int32_t* shortlist, int64_t B, int k_h,
     hipStream_t st = static_cast<hipStream_t>(stream);
     XC_LAUNCH(K_SAMPLE, st, (sample_kernel<<<dim3(static_cast<unsigned>(B)), kSampleThreads, 0, st>>>(
         shortlist, k_h, k_r, L, seed, n2, neg, logq)));
+    XC_HIP_CHECK(hipGetLastError());
+    return XC_OK;
+}
+
+extern "C" int xc_sample_negatives_mixture(const int32_t* shortlist, const float* scores, int64_t B, int M,
+                                           int k_h, int k_r, int64_t L, uint64_t seed, int32_t* neg,
+                                           float* logq, void* stream) {
+    using namespace xc;
+    if (B < 1 || B > 0x7fffffffLL || M < 1 || M > XC_MAX_K_SAMPLE) return XC_ESHAPE;
+    if (k_h < 0 || k_r < 0 || k_h + k_r < 1 || L < 1 || L > 0x7fffffffLL) return XC_ESHAPE;
+    if (!shortlist || !scores || !neg || !logq) return XC_EINVAL;
+    int n2 = 2;
+    while (n2 < M) n2 <<= 1;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_SAMPLE, st, (sample_mixture_kernel<<<dim3(static_cast<unsigned>(B)), kSampleThreads, 0, st>>>(
+        shortlist, scores, M, k_h, k_r, L, seed, n2, neg, logq)));
     XC_HIP_CHECK(hipGetLastError());
     return XC_OK;
 }
