@@ -620,6 +620,28 @@ struct MinePlan {
 
 static int slices_cap(int kcap) { return kcap <= 64 ? kMaxSlices : kMaxSlices / 2; }    // slices per phase at most
 
+// Number of label tiles of the phase that starts at tile `lo`.  Phases end at powers of the growth
+// factor (1, 8, 64, ... tiles seen).  A phase of fewer than 8 tiles deals its items (query tile,
+// label tile) to the workgroups in plain order, so it is shortened by up to a third if the number
+// of items then comes out just under a multiple of the grid.
+static int64_t phase_tiles(int64_t lo, int64_t nQT) {
+    if (lo == 0) return 1;
+    int64_t end = kPhaseGrowth;
+    while (end < 2 * lo) end *= kPhaseGrowth;           // a shortened phase still ends in this decade
+    const int64_t want = end - lo;
+    if (want >= kXcds) return want;
+    int64_t best = want;
+    double best_fill = 0.0;
+    for (int64_t n = (2 * want + 2) / 3; n <= want; ++n) {
+        if (n < 1) continue;
+        const int64_t items = nQT * n;
+        const int64_t rounds = (items + kMineGrid - 1) / kMineGrid;
+        const double fill = static_cast<double>(items) / static_cast<double>(rounds * kMineGrid);
+        if (fill >= best_fill) { best_fill = fill; best = n; }
+    }
+    return best;
+}
+
 static int plan_mine(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, MinePlan* p) {
     if (t != XC_F32 && t != XC_BF16) return XC_EINVAL;
     if (Zq < 1 || L < 1 || d < 1 || k_h < 1 || k_h > XC_MAX_K_MINE || k_h > L) return XC_ESHAPE;
@@ -711,8 +733,8 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
 
     int64_t lo = 0;
     while (lo < p.nLT) {
-        // phase sizes 1, 7, 56, ... tiles: each phase sees 8x the labels seen before it
-        int64_t hi = lo == 0 ? 1 : lo * kPhaseGrowth;
+        // phases end at about 1, 8, 64, ... tiles: each sees about 8x the labels seen before it
+        int64_t hi = lo + phase_tiles(lo, p.nQT);
         if (hi > p.nLT || p.nLT - hi < hi / 4) hi = p.nLT;      // fold a short remainder into this phase
         const int64_t nT = hi - lo;
         if (nT >= kXcds) {
