@@ -60,6 +60,11 @@ def test_host_side_argument_checks(lib):
     # null pointers / k_h >= L are rejected without a launch
     assert b.xc_sample_negatives(None, 4, 8, 16, 8, 1, None, None, None) == -2
     assert b.xc_sample_negatives(None, 4, 8, 16, 100, 1, None, None, None) == -1
+    assert b.xc_sample_negatives_mixture(None, None, 4, 0, 8, 16, 100, 1, None, None, None) == -2      # M < 1
+    assert b.xc_sample_negatives_mixture(None, None, 4, 2000, 8, 16, 100, 1, None, None, None) == -2   # M too wide
+    assert b.xc_sample_negatives_mixture(None, None, 4, 12, 8, 16, 100, 1, None, None, None) == -1     # null pointers
+    assert b.xc_mfma_probe(None, 10, 1, None, None) == -1
+    assert b.xc_copy_probe(None, None, 64, None) == -1
     assert b.xc_mine_negatives(None, None, 1, 100, 64, 8, 1, None, None, None, 0, None) == -1
     assert b.xc_step(None, None, 32, 4096, 64, None, 1, None, None, 24, 0.1, 0, 0, None, None, None,
                      None, None, None, big, None) == -1
