@@ -23,6 +23,7 @@
 //       candidate list to its best k and publishes the new tau; after the last
 //       phase it sorts the winners by (score descending, id ascending).
 #include <mutex>
+#include <type_traits>
 
 #include "xc_common.h"
 
@@ -191,8 +192,33 @@ __device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_addr /*
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :: "v"(gptr), "s"(lds_addr) : "memory");
 }
+// The same with a wave-uniform 64-bit base and a 32-bit lane offset: no vector arithmetic is needed
+// to form the address, so issuing the load never competes with another wave's MFMAs for the VALU.
+template <int kLdsOffset>
+__device__ __forceinline__ void lds_dma16_sbase(const void* sbase /* wave-uniform */, uint32_t voff,
+                                                uint32_t lds_addr /* wave-uniform; kLdsOffset is added */) {
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr), "n"(kLdsOffset) : "memory", "scc");
+}
 __device__ __forceinline__ void wait_all_vmem() {
     __builtin_amdgcn_s_waitcnt(0x0070 | 0x0f00);      // vmcnt(0); expcnt and lgkmcnt untouched
+}
+
+// Stage fill of a ragged tile (rows past the end repeat the last row) or of rows whose length is
+// not a multiple of the stage (chunks past the end come from the zero block): lane addresses are
+// formed one by one.  Kept out of line so that its registers do not burden the main loop.
+template <bool KTAIL>
+__device__ __noinline__ void issue_stage_slow(const unsigned char* base, int64_t last_row, int64_t row_bytes,
+                                              uint32_t kb, int drow, uint32_t dcol0, uint32_t dcol1,
+                                              uint32_t dst, const unsigned char* zeros) {
+#pragma unroll 1
+    for (int t = 0; t < 16; ++t) {
+        const int64_t r = drow + 8 * t;
+        const uint32_t dc = (t & 1) ? dcol1 : dcol0;
+        const unsigned char* g = base + ((r < last_row ? r : last_row) * row_bytes + dc + kb);
+        if (KTAIL && kb + dc >= static_cast<uint32_t>(row_bytes)) g = zeros;
+        lds_dma16(g, __builtin_amdgcn_readfirstlane(dst + t * 1024));
+    }
 }
 
 template <typename T, bool KTAIL>
@@ -233,14 +259,21 @@ void mine_tile_kernel(const MineArgs a) {
     const int frag_a = (wm * 128 + (lane & 31)) * kStageBytes + (((lane >> 5) ^ swz) * 16);
     const int frag_b = (kBM + wn * 64 + (lane & 31)) * kStageBytes + (((lane >> 5) ^ swz) * 16);
 
-    // ---- stage fill: waves 0..3 bring the W rows 64 (wave & 3) .. + 63, waves 4..7 the Z rows;
-    // instruction t of a wave covers rows 8 t .. 8 t + 7 of its 64, lane i -> row i / 8, position i % 8.
-    // The chunk a lane fetches is position ^ swizzle(row), which depends on t only through t & 1.
-    const bool dma_z = wave >= 4;
-    const int drow = (wave & 3) * 64 + (lane >> 3);
+    // ---- stage fill.  A stage is brought in by four waves, one per SIMD, while their SIMD-mates
+    // (waves w and w + 4 share a SIMD) start on the MFMAs at once; the two halves of the workgroup
+    // take turns from stage to stage.  The issuing waves wait in the texture unit's queue, not in
+    // front of the matrix pipe.  Wave w (and w + 4) owns 128 rows: W rows 0..127 / 128..255 for
+    // w & 3 = 0 / 1, Z rows likewise for 2 / 3; instruction t covers rows 8 t .. 8 t + 7 of them,
+    // lane i -> row i / 8, position i % 8.  The chunk a lane fetches is position ^ swizzle(row),
+    // which depends on t only through t & 1.
+    constexpr int kDmaInstr = 16;
+    const bool dma_z = (wave & 3) >= 2;
+    const int drow = (wave & 1) * 128 + (lane >> 3);
     const uint32_t dcol[2] = {static_cast<uint32_t>(((lane & 7) ^ (lane >> 4)) * 16),
                               static_cast<uint32_t>(((lane & 7) ^ ((lane >> 4) + 4)) * 16)};
-    const uint32_t dma_dst = lds_base + (dma_z ? kBM * kStageBytes : 0) + (wave & 3) * 64 * kStageBytes;
+    const uint32_t dma_dst = lds_base + (dma_z ? kBM * kStageBytes : 0) + (wave & 1) * 128 * kStageBytes;
+    const uint32_t voff[2] = {static_cast<uint32_t>(drow * a.row_bytes) + dcol[0],
+                              static_cast<uint32_t>((drow + 8) * a.row_bytes) + dcol[1]};
 
     for (; item < item_end; item += item_step) {
         const int64_t qtile = a.Qx > 0 ? item : item / a.S;
@@ -254,31 +287,39 @@ void mine_tile_kernel(const MineArgs a) {
 
         // ---- the load stream runs one stage ahead of the compute stream and stops at the last stage
         const unsigned char* zbase = a.Z + q0 * a.row_bytes;
-        uint32_t roff[8];             // source byte offset of this lane's chunk, per instruction
-        auto set_rows = [&](int64_t last_row) {              // rows past the end repeat the last row
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const int64_t r = drow + 8 * t;
-                roff[t] = static_cast<uint32_t>((r < last_row ? r : last_row) * a.row_bytes) + dcol[t & 1];
-            }
-        };
-        if (dma_z) set_rows(a.Zq - 1 - q0);
         int64_t ld_tile = t_begin;
         int ld_kb = 0, ld_slot = 0;
         int64_t to_issue = (t_end - t_begin) * a.nkb;
         auto issue_stage = [&]() {
-            const unsigned char* base = zbase;
-            if (!dma_z) {
-                if (ld_kb == 0) set_rows(a.L - 1 - ld_tile * kBM);
-                base = a.W + ld_tile * kBM * a.row_bytes;
-            }
+            const int64_t last_row = dma_z ? a.Zq - 1 - q0 : a.L - 1 - ld_tile * kBM;
+            const unsigned char* base = dma_z ? zbase : a.W + ld_tile * kBM * a.row_bytes;
             const uint32_t kb = static_cast<uint32_t>(ld_kb) * kStageBytes;
             const uint32_t dst = dma_dst + static_cast<uint32_t>(ld_slot) * kStageBuf;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const unsigned char* g = base + (roff[t] + kb);
-                if (KTAIL && kb + dcol[t & 1] >= static_cast<uint32_t>(a.row_bytes)) g = a.zeros;
-                lds_dma16(g, dst + t * 1024);
+            if ((wave < 4) == (ld_slot == 0)) {              // this half's turn
+                if (!KTAIL && last_row >= kBM - 1) {
+                    // the usual case: every row of the tile exists.  Lane offsets voff[t & 1] are the
+                    // same for all stages; everything else is added to the scalar base.
+                    const uint64_t b64 = reinterpret_cast<uint64_t>(base + kb);     // wave-uniform
+                    // (readfirstlane returns a signed int: widen each half as unsigned)
+                    const uint64_t sb =
+                        (static_cast<uint64_t>(static_cast<uint32_t>(
+                             __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32)))) << 32) |
+                        static_cast<uint64_t>(static_cast<uint32_t>(
+                            __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64))));
+                    const uint64_t pair_step = 16u * static_cast<uint64_t>(a.row_bytes);     // 16 rows per two instructions
+                    auto pair = [&](auto tc) {
+                        constexpr int t = decltype(tc)::value;
+                        const unsigned char* sp = reinterpret_cast<const unsigned char*>(sb + (t >> 1) * pair_step);
+                        lds_dma16_sbase<t * 1024>(sp, voff[0], dst);
+                        lds_dma16_sbase<(t + 1) * 1024>(sp, voff[1], dst);
+                    };
+                    pair(std::integral_constant<int, 0>{});  pair(std::integral_constant<int, 2>{});
+                    pair(std::integral_constant<int, 4>{});  pair(std::integral_constant<int, 6>{});
+                    pair(std::integral_constant<int, 8>{});  pair(std::integral_constant<int, 10>{});
+                    pair(std::integral_constant<int, 12>{}); pair(std::integral_constant<int, 14>{});
+                } else {
+                    issue_stage_slow<KTAIL>(base, last_row, a.row_bytes, kb, drow, dcol[0], dcol[1], dst, a.zeros);
+                }
             }
             ld_slot ^= 1;
             --to_issue;
