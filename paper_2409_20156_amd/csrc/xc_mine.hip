@@ -334,32 +334,60 @@ void mine_tile_kernel(const MineArgs a) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.0f;
 
+        // ---- main loop.  At the top of a stage its data is visible in LDS, the next stage's loads
+        // have been issued into the other buffer, and the fragments of its first k-step are already
+        // in registers.  The barrier that publishes the next stage sits before the last k-step's
+        // MFMAs, so the first fragment reads of the next stage (and the loads of the stage after it)
+        // are under way while those MFMAs run.
+        uint4 fa[2][4], fb[2][2];
+        auto read_frags = [&](const unsigned char* buf, int kk, int sel) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+                fa[sel][mt] = *reinterpret_cast<const uint4*>(buf + ((frag_a ^ (kk * 32)) + mt * 32 * kStageBytes));
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+                fb[sel][nt] = *reinterpret_cast<const uint4*>(buf + ((frag_b ^ (kk * 32)) + nt * 32 * kStageBytes));
+        };
+        auto products = [&](int sel) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    MineTraits<T>::mma(fa[sel][mt], fb[sel][nt], acc[mt][nt]);
+        };
+        int buf_sel = 0;
+        auto publish_next = [&](const unsigned char* next_buf) {
+            wait_all_vmem();                                 // this wave's part of the next stage has landed
+            __syncthreads();                                 // everyone's has; the current buffer is free
+            if (to_issue > 0) issue_stage();                 // the stage after it, into the current buffer
+            read_frags(next_buf, 0, 0);
+        };
+
         __syncthreads();                                     // tau/cnt visible; both stage buffers free
         issue_stage();
+        publish_next(smem);                                  // stage 0 visible, stage 1 under way
 
-        int buf_sel = 0;
         for (int64_t tile = t_begin; tile < t_end; ++tile) {
             for (int kb = 0; kb < a.nkb; ++kb) {
-                wait_all_vmem();                             // this wave's part of the stage has landed
-                __syncthreads();                             // everyone's has; the other buffer is free
-                if (to_issue > 0) issue_stage();
                 const unsigned char* cur = smem + buf_sel * kStageBuf;
+                const unsigned char* nxt = smem + (buf_sel ^ 1) * kStageBuf;
                 buf_sel ^= 1;
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    uint4 fa[4], fb[2];
-#pragma unroll
-                    for (int mt = 0; mt < 4; ++mt)
-                        fa[mt] = *reinterpret_cast<const uint4*>(cur + ((frag_a ^ (kk * 32)) + mt * 32 * kStageBytes));
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        fb[nt] = *reinterpret_cast<const uint4*>(cur + ((frag_b ^ (kk * 32)) + nt * 32 * kStageBytes));
-#pragma unroll
-                    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                        for (int nt = 0; nt < 2; ++nt)
-                            MineTraits<T>::mma(fa[mt], fb[nt], acc[mt][nt]);
-                }
+                read_frags(cur, 1, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                products(0);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(cur, 2, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                products(1);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(cur, 3, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                products(0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (kb + 1 < a.nkb) publish_next(nxt);       // within a tile: before the last products
+                __builtin_amdgcn_sched_barrier(0);
+                products(1);
+                __builtin_amdgcn_sched_barrier(0);
             }
 
             // ---- threshold filter: lane owns query column (lane & 31) of each N tile.  A score that
@@ -519,6 +547,9 @@ void mine_tile_kernel(const MineArgs a) {
                 }
             }
             __syncthreads();
+            // the stash is done with: the next tile's first stage (its loads went out during this
+            // tile's last stage) is published now
+            if (tile + 1 < t_end) publish_next(smem + buf_sel * kStageBuf);
         }
     }
 }
