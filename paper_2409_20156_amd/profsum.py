@@ -3,11 +3,15 @@
   python -m paper_2409_20156_amd.profsum stats  <kernel_stats.csv> <out.md> "<title>" "<command>"
   python -m paper_2409_20156_amd.profsum pmc    <workload> <fetch counter csv> <write counter csv>
                                                 <copy MiB> <out.md> <traffic.json> "<commands>"
+  python -m paper_2409_20156_amd.profsum sq     <counter csv> <out.md> "<title>" "<command>"
 
 `stats` lists the library's kernels from a `--kernel-trace --stats` run.  `pmc` averages
 FETCH_SIZE and WRITE_SIZE (KiB per dispatch) per library kernel, scales each by what the same
 counter read for the plain copy kernel of known size in the same run, and writes bytes per
-launch into the JSON file the benchmark reads.
+launch into the JSON file the benchmark reads.  `sq` turns one run with the shader counters
+SQ_VALU_MFMA_BUSY_CYCLES, SQ_INSTS_VALU_MFMA_MOPS_BF16, SQ_BUSY_CU_CYCLES, SQ_WAVE_CYCLES, SQ_WAIT_ANY
+and GRBM_GUI_ACTIVE into matrix-pipe utilisation, the share of their time waves spend waiting, and
+the shader clock.
 """
 from __future__ import annotations
 
@@ -22,7 +26,9 @@ KERNELS = {"mine_tile_kernel": "mine_tile", "mine_select_kernel": "mine_select",
            "sample_kernel": "sample", "gather_kernel": "gather", "radix_count_kernel": "radix_count",
            "radix_prefix_kernel": "radix_scan", "radix_scatter_kernel": "radix_scatter",
            "heads_count_kernel": "heads_count", "heads_write_kernel": "heads_write",
-           "update_kernel": "update", "copy_probe_kernel": "copy_probe"}
+           "update_kernel": "update", "copy_probe_kernel": "copy_probe", "mfma_probe_kernel": "mfma_probe"}
+
+kXcds, kSimds = 8, 1024          # MI355X: one GRBM per XCD; 256 CUs x 4 SIMDs
 
 
 def short_name(full: str):
@@ -95,10 +101,60 @@ def pmc(workload, fetch_csv, write_csv, copy_mib, out, traffic_json, cmd):
     json.dump(data, open(traffic_json, "w"), indent=1, sort_keys=True)
 
 
+def sq(src, out, title, cmd):
+    """Per kernel, over all its dispatches: sums of the counters and of the durations.
+
+    GRBM_GUI_ACTIVE is reported summed over the 8 XCDs, in shader clocks, and covers the dispatch plus
+    about 12 us of counter set-up, so the clock is taken from dispatches longer than 0.4 ms only.
+    SQ_VALU_MFMA_BUSY_CYCLES is in clocks summed over SIMDs (32 per 32x32x16 bf16 MFMA: its 8 passes);
+    SQ_BUSY_CU_CYCLES, SQ_WAVE_CYCLES and SQ_WAIT_ANY are in units of 4 clocks.
+    """
+    tot = defaultdict(lambda: defaultdict(float))
+    dur = defaultdict(dict)
+    for r in csv.DictReader(open(src)):
+        n = short_name(r["Kernel_Name"])
+        if n is None:
+            continue
+        tot[n][r["Counter_Name"]] += float(r["Counter_Value"])
+        dur[n][r["Dispatch_Id"]] = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"]), r["Dispatch_Id"])
+    long_gui = defaultdict(float)
+    long_ns = defaultdict(float)
+    for r in csv.DictReader(open(src)):
+        n = short_name(r["Kernel_Name"])
+        if n is None or r["Counter_Name"] != "GRBM_GUI_ACTIVE":
+            continue
+        ns = dur[n][r["Dispatch_Id"]][0]
+        if ns > 400000:
+            long_gui[n] += float(r["Counter_Value"]) / kXcds
+            long_ns[n] += ns
+    with open(out, "w") as f:
+        f.write("# %s\n\nCommand (on the MI355X box, from the repository root):\n\n```\n%s\n```\n\n" % (title, cmd))
+        f.write("Sums over all dispatches of a kernel. *matrix pipe busy* = SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x "
+                "GRBM_GUI_ACTIVE / 8 XCDs), the profiler's own MfmaUtil formula; *of CU-busy time* divides by "
+                "4 x SQ_BUSY_CU_CYCLES instead (leaves out launch ramps and idle CUs); *waves waiting* = SQ_WAIT_ANY / "
+                "SQ_WAVE_CYCLES; *MFMA TFLOP* = 512 x SQ_INSTS_VALU_MFMA_MOPS_BF16; *clock* = GRBM_GUI_ACTIVE / 8 / "
+                "duration over the dispatches longer than 0.4 ms.\n\n")
+        f.write("| kernel | dispatches | total ms | MFMA TFLOP | matrix pipe busy | of CU-busy time | waves waiting | clock GHz |\n"
+                "|---|---|---|---|---|---|---|---|\n")
+        for n in sorted(tot, key=lambda n: -sum(d[0] for d in dur[n].values())):
+            c = tot[n]
+            ns = sum(d[0] for d in dur[n].values())
+            gui = c["GRBM_GUI_ACTIVE"] / kXcds
+            busy = 4.0 * c["SQ_BUSY_CU_CYCLES"]          # clocks summed over SIMDs
+            clock = "%.2f" % (long_gui[n] / long_ns[n]) if long_ns[n] else "-"
+            f.write("| %s | %d | %.3f | %.3f | %.3f | %.3f | %.3f | %s |\n"
+                    % (n, len(dur[n]), ns / 1e6, 512.0 * c["SQ_INSTS_VALU_MFMA_MOPS_BF16"] / 1e12,
+                       c["SQ_VALU_MFMA_BUSY_CYCLES"] / (kSimds * gui) if gui else 0.0,
+                       c["SQ_VALU_MFMA_BUSY_CYCLES"] / busy if busy else 0.0,
+                       c["SQ_WAIT_ANY"] / c["SQ_WAVE_CYCLES"] if c["SQ_WAVE_CYCLES"] else 0.0, clock))
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 2 and sys.argv[1] == "stats":
         stats(*sys.argv[2:6])
     elif len(sys.argv) >= 2 and sys.argv[1] == "pmc":
         pmc(*sys.argv[2:9])
+    elif len(sys.argv) >= 2 and sys.argv[1] == "sq":
+        sq(*sys.argv[2:6])
     else:
         sys.exit(__doc__)
