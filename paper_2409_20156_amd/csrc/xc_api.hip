@@ -12,7 +12,7 @@ void set_last_hip_error(hipError_t e) { g_last_hip_error = static_cast<int>(e); 
 
 static const char* const kKernelNames[K_NUM_KERNELS] = {
     "mine_tile", "mine_select", "sample", "gather", "radix_count", "radix_scan",
-    "radix_scatter", "heads_count", "heads_write", "update"};
+    "radix_scatter", "bucket_sort", "heads_count", "heads_write", "update"};
 
 struct Pending { int id; hipEvent_t start, stop; };
 static std::mutex g_mu;

@@ -26,7 +26,7 @@ void set_last_hip_error(hipError_t e);
 // ---- optional per-kernel event timing ----------------------------------------
 enum KernelId {
     K_MINE_TILE = 0, K_MINE_SELECT, K_SAMPLE, K_GATHER, K_RADIX_COUNT, K_RADIX_SCAN,
-    K_RADIX_SCATTER, K_HEADS_COUNT, K_HEADS_WRITE, K_UPDATE, K_NUM_KERNELS
+    K_RADIX_SCATTER, K_BUCKET_SORT, K_HEADS_COUNT, K_HEADS_WRITE, K_UPDATE, K_NUM_KERNELS
 };
 bool profile_on();
 void profile_mark(int kernel_id, hipStream_t st, bool begin);

@@ -394,16 +394,26 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
 }
 
 // ---------------------------------------------------------------------------
-// stable LSD radix sort of (key, value) pairs, `rb` bits per pass (rb <= 11).
+// stable radix sort of (key, value) pairs, at most 11 bits per digit.
 // Block b owns the contiguous chunk [b*chunk, (b+1)*chunk) of the input.
 //   radix_count    per-block digit histogram -> counts[digit][block]
 //   radix_prefix   one wave per digit: exclusive prefix over the blocks, digit total
 //   radix_scatter  digit bases by a scan of the totals inside every block, then the
 //                  block walks its chunk tile by tile with running digit offsets
+//   bucket_sort    one workgroup per value of the high digit: histogram, scan and stable
+//                  placement by the low digit inside that bucket, no global counts
+// Keys of at most 22 bits take one count/prefix/scatter round on the high digit and then
+// bucket_sort (5 launches with the segment heads instead of 8); wider keys take
+// least-significant-digit-first rounds of count/prefix/scatter.
+// A key >= inv_key (the marker of a masked pair) is given the digit inv_digit.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ int digit_of(uint32_t key, int shift, int radix, uint32_t inv_key, int inv_digit) {
+    return key >= inv_key ? inv_digit : static_cast<int>((key >> shift) & static_cast<uint32_t>(radix - 1));
+}
+
 __global__ __launch_bounds__(256)
 void radix_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t chunk, int shift, int rb,
-                        int nb, int* __restrict__ counts /* [radix][nb] */) {
+                        int nb, int* __restrict__ counts /* [radix][nb] */, uint32_t inv_key, int inv_digit) {
     __shared__ int hist[kMaxRadix];
     const int radix = 1 << rb;
     for (int d = threadIdx.x; d < radix; d += 256) hist[d] = 0;
@@ -412,7 +422,7 @@ void radix_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
     int64_t p1 = p0 + chunk;
     p1 = p1 < P ? p1 : P;
     for (int64_t p = p0 + threadIdx.x; p < p1; p += 256)
-        atomicAdd(&hist[(keys[p] >> shift) & (radix - 1)], 1);
+        atomicAdd(&hist[digit_of(keys[p], shift, radix, inv_key, inv_digit)], 1);
     __syncthreads();
     for (int d = threadIdx.x; d < radix; d += 256) counts[d * nb + blockIdx.x] = hist[d];
 }
@@ -433,11 +443,51 @@ void radix_prefix_kernel(int* __restrict__ counts /* [radix][nb], in place */, i
     if (lane == 0) totals[blockIdx.x] = run;
 }
 
+// One tile of kSortTile keys: key/val of thread tid (valid or not) goes to offs[digit] + its rank among
+// the tile's keys of the same digit, and offs moves on.  whist must be zero on entry and is zero on exit.
+__device__ __forceinline__ void place_tile(bool valid, uint32_t key, uint32_t val, int digit, int rb,
+                                           int* offs, int (*whist)[kMaxRadix],
+                                           uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out) {
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    // lanes of this wave holding the same digit
+    uint64_t same = __ballot(valid);
+    for (int b = 0; b < rb; ++b) {
+        const bool bit = (digit >> b) & 1;
+        const uint64_t bal = __ballot(bit);
+        same &= bit ? bal : ~bal;
+    }
+    const int rank = __popcll(same & lanemask_lt());
+    if (valid && rank == 0) whist[wave][digit] = __popcll(same);
+    __syncthreads();
+    if (valid) {
+        int before = offs[digit];
+        for (int w = 0; w < wave; ++w) before += whist[w][digit];
+        keys_out[before + rank] = key;
+        vals_out[before + rank] = val;
+    }
+    __syncthreads();
+    // only digits present in this tile need their running offset advanced
+    if (valid && rank == 0) {
+        int add = 0;
+#pragma unroll
+        for (int w = 0; w < kSortTile / kWave; ++w) add += whist[w][digit];
+        // one lane per (wave, digit); the wave holding the lowest index among the waves
+        // that saw the digit applies the update
+        bool first = true;
+        for (int w = 0; w < wave; ++w) first = first && whist[w][digit] == 0;
+        if (first) offs[digit] += add;
+    }
+    __syncthreads();
+    if (valid && rank == 0) whist[wave][digit] = 0;
+    __syncthreads();
+}
+
 __global__ __launch_bounds__(kSortTile)
 void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
                           uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, int64_t P,
                           int64_t chunk, int shift, int rb, int nb, const int* __restrict__ prefix,
-                          const int* __restrict__ totals) {
+                          const int* __restrict__ totals, uint32_t inv_key, int inv_digit) {
     __shared__ int offs[kMaxRadix];
     __shared__ int whist[kSortTile / kWave][kMaxRadix];
     __shared__ int wsum[kSortTile / kWave];
@@ -471,38 +521,110 @@ void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* 
         const bool valid = p < p1;
         uint32_t key = 0, val = 0;
         if (valid) { key = keys_in[p]; val = vals_in[p]; }
-        const int digit = (key >> shift) & (radix - 1);
-        // lanes of this wave holding the same digit
-        uint64_t same = __ballot(valid);
-        for (int b = 0; b < rb; ++b) {
-            const bool bit = (digit >> b) & 1;
-            const uint64_t bal = __ballot(bit);
-            same &= bit ? bal : ~bal;
-        }
-        const int rank = __popcll(same & lanemask_lt());
-        if (valid && rank == 0) whist[wave][digit] = __popcll(same);
-        __syncthreads();
-        if (valid) {
-            int before = offs[digit];
-            for (int w = 0; w < wave; ++w) before += whist[w][digit];
-            keys_out[before + rank] = key;
-            vals_out[before + rank] = val;
-        }
-        __syncthreads();
-        // only digits present in this tile need their running offset advanced
-        if (valid && rank == 0) {
-            int add = 0;
+        place_tile(valid, key, val, digit_of(key, shift, radix, inv_key, inv_digit), rb, offs, whist, keys_out, vals_out);
+    }
+}
+
+// All pairs whose key has high digit blockIdx.x (they are contiguous after the scatter on that digit,
+// in their original order): stable placement by the low `rb` bits.  A bucket of up to
+// kBucketRegTiles tiles is read once and kept in registers.  Every non-empty bin is one label, so
+// the number of segment heads of the bucket falls out of the histogram.
+constexpr int kBucketRegTiles = 8;
+#ifndef XC_BUCKET_TARGET
+#define XC_BUCKET_TARGET 512
+#endif
+constexpr int64_t kBucketTarget = XC_BUCKET_TARGET;   // pairs per bucket the digit split aims at
+
+__global__ __launch_bounds__(kSortTile)
+void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
+                        uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out,
+                        const int* __restrict__ sizes /* [gridDim.x] pairs per bucket */, int rb,
+                        int* __restrict__ head_cnt /* [gridDim.x] */) {
+    __shared__ int offs[kMaxRadix];
+    __shared__ int whist[kSortTile / kWave][kMaxRadix];
+    __shared__ int wsum[kSortTile / kWave];
+    __shared__ int red[kSortTile];
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int radix = 1 << rb;
+    const int b = blockIdx.x;
+    {   // where the bucket starts: the sizes of the buckets before it
+        int t = 0;
+        for (int j = tid; j < b; j += kSortTile) t += sizes[j];
+        red[tid] = t;
+    }
+    for (int d = tid; d < radix; d += kSortTile) {
+        offs[d] = 0;
 #pragma unroll
-            for (int w = 0; w < kSortTile / kWave; ++w) add += whist[w][digit];
-            // one lane per (wave, digit); the wave holding the lowest index among the waves
-            // that saw the digit applies the update
-            bool first = true;
-            for (int w = 0; w < wave; ++w) first = first && whist[w][digit] == 0;
-            if (first) offs[digit] += add;
+        for (int w = 0; w < kSortTile / kWave; ++w) whist[w][d] = 0;
+    }
+    __syncthreads();
+    for (int s2 = kSortTile / 2; s2 > 0; s2 >>= 1) {
+        if (tid < s2) red[tid] += red[tid + s2];
+        __syncthreads();
+    }
+    const int p0 = red[0];
+    const int p1 = p0 + sizes[b];
+    __syncthreads();                                   // red is reused below
+    const bool in_regs = p1 - p0 <= kBucketRegTiles * kSortTile;        // uniform
+    uint32_t rk[kBucketRegTiles], rv[kBucketRegTiles];
+    if (in_regs) {
+#pragma unroll
+        for (int u = 0; u < kBucketRegTiles; ++u) {
+            const int p = p0 + u * kSortTile + tid;
+            rk[u] = 0; rv[u] = 0;
+            if (p < p1) { rk[u] = keys_in[p]; rv[u] = vals_in[p]; }
+        }
+#pragma unroll
+        for (int u = 0; u < kBucketRegTiles; ++u)
+            if (p0 + u * kSortTile + tid < p1) atomicAdd(&offs[rk[u] & static_cast<uint32_t>(radix - 1)], 1);
+    } else {
+        for (int p = p0 + tid; p < p1; p += kSortTile) atomicAdd(&offs[keys_in[p] & static_cast<uint32_t>(radix - 1)], 1);
+    }
+    __syncthreads();
+    {   // bins -> start positions (exclusive scan, contiguous bins per thread); heads = non-empty bins
+        const int per = (radix + kSortTile - 1) / kSortTile;        // <= 8
+        int cnt[kMaxRadix / kSortTile];
+        int local = 0, nz = 0;
+        for (int j = 0; j < per; ++j) {
+            const int d = tid * per + j;
+            const int c = d < radix ? offs[d] : 0;
+            cnt[j] = c; local += c; nz += c > 0 ? 1 : 0;
+        }
+        const int incl = wave_incl_scan(local);
+        if ((tid & 63) == 63) wsum[wave] = incl;
+        red[tid] = nz;
+        __syncthreads();
+        int run = p0 + incl - local;
+        for (int w = 0; w < wave; ++w) run += wsum[w];
+        for (int j = 0; j < per; ++j) {
+            const int d = tid * per + j;
+            if (d < radix) { offs[d] = run; run += cnt[j]; }
+        }
+        for (int s2 = kSortTile / 2; s2 > 0; s2 >>= 1) {
+            __syncthreads();
+            if (tid < s2) red[tid] += red[tid + s2];
         }
         __syncthreads();
-        if (valid && rank == 0) whist[wave][digit] = 0;
-        __syncthreads();
+        if (tid == 0) head_cnt[b] = red[0];
+    }
+    if (in_regs) {
+#pragma unroll
+        for (int u = 0; u < kBucketRegTiles; ++u) {
+            if (p0 + u * kSortTile >= p1) break;                       // uniform
+            const bool valid = p0 + u * kSortTile + tid < p1;
+            place_tile(valid, rk[u], rv[u], static_cast<int>(rk[u] & static_cast<uint32_t>(radix - 1)), rb, offs, whist,
+                       keys_out, vals_out);
+        }
+    } else {
+        for (int t0 = p0; t0 < p1; t0 += kSortTile) {
+            const int p = t0 + tid;
+            const bool valid = p < p1;
+            uint32_t key = 0, val = 0;
+            if (valid) { key = keys_in[p]; val = vals_in[p]; }
+            place_tile(valid, key, val, static_cast<int>(key & static_cast<uint32_t>(radix - 1)), rb, offs, whist,
+                       keys_out, vals_out);
+        }
     }
 }
 
@@ -541,11 +663,25 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
                         const uint32_t* __restrict__ vals, int32_t* __restrict__ touched,
                         int32_t* __restrict__ seg_start, uint32_t* __restrict__ seg_idx0,
                         int32_t* __restrict__ n_touched, const float* __restrict__ loss_q, int64_t B,
-                        float inv_B, float* __restrict__ loss, int SQ) {
+                        float inv_B, float* __restrict__ loss, int SQ,
+                        const int* __restrict__ bucket_sizes /* not null: block b covers bucket b */) {
     __shared__ int sh[256];
     __shared__ int wcnt[4];
     __shared__ int running;
+    __shared__ int bucket_p0;
     const int tid = threadIdx.x;
+    if (bucket_sizes) {                 // first position of this block's bucket
+        int t0 = 0;
+        for (int b = tid; b < static_cast<int>(blockIdx.x); b += 256) t0 += bucket_sizes[b];
+        sh[tid] = t0;
+        __syncthreads();
+        for (int s = 128; s > 0; s >>= 1) {
+            if (tid < s) sh[tid] += sh[tid + s];
+            __syncthreads();
+        }
+        if (tid == 0) bucket_p0 = sh[0];
+        __syncthreads();
+    }
     // heads in the blocks before this one
     int t = 0;
     for (int b = tid; b < static_cast<int>(blockIdx.x); b += 256) t += head_cnt[b];
@@ -580,8 +716,9 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
         }
         if (tid == 0) loss[0] = shf[0] * inv_B;
     }
-    const int64_t p0 = blockIdx.x * chunk;
+    int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
+    if (bucket_sizes) { p0 = bucket_p0; p1 = p0 + bucket_sizes[blockIdx.x]; }
     p1 = p1 < P ? p1 : P;
     for (int64_t t0 = p0; t0 < p1; t0 += 256) {
         const int64_t p = t0 + tid;
@@ -864,6 +1001,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
 struct StepPlan {
     int64_t P;
     int n, G, cpl, nb, passes, rb, key_bits, sq, n_shift;
+    int low_bits, n_buckets, high_rb;       // n_buckets > 0: one round on the high digit, then bucket_sort
     uint32_t n_magic;
     int64_t chunk;
     size_t off_keys0, off_keys1, off_vals0, off_vals1, off_g, off_lossq, off_dzpart, off_counts, off_totals, off_headcnt,
@@ -907,6 +1045,23 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     p->key_bits = bits;                                // keys take values 0..L
     p->passes = (bits + kMaxRadixBits - 1) / kMaxRadixBits;
     p->rb = (bits + p->passes - 1) / p->passes;          // digit width, <= 11 bits
+    // Keys of up to 22 bits: split so that a bucket of the high digit holds about 256 pairs (the pairs
+    // spread over the labels), within what the kernels hold: low digit <= 11 bits, and the high digit,
+    // with one more value for the masked pairs, < 2^11.
+    p->n_buckets = 0; p->low_bits = 0; p->high_rb = 0;
+    if (L >= 2 && bits <= 2 * kMaxRadixBits) {
+        int low = 1;
+        while (low < kMaxRadixBits && (L >> low) * kBucketTarget > p->P) ++low;
+        while (low < kMaxRadixBits && ((L - 1) >> low) + 2 > kMaxRadix - 1) ++low;
+        const int64_t nbk = ((L - 1) >> low) + 1;
+        if (nbk + 1 <= kMaxRadix - 1) {
+            p->low_bits = low;
+            p->n_buckets = static_cast<int>(nbk);
+            int hb = 1;
+            while ((static_cast<int64_t>(1) << hb) <= nbk) ++hb;       // digits 0..nbk fit
+            p->high_rb = hb;
+        }
+    }
     size_t off = 0;
     auto take = [&off](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
     const size_t P = static_cast<size_t>(p->P);
@@ -919,7 +1074,7 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     p->off_dzpart = take(p->sq > 1 ? static_cast<size_t>(B) * p->sq * d * 4 : 0);
     p->off_counts = take(static_cast<size_t>(kMaxRadix) * nb * 4);
     p->off_totals = take(static_cast<size_t>(kMaxRadix) * 4);
-    p->off_headcnt = take(static_cast<size_t>(nb) * 4);
+    p->off_headcnt = take(static_cast<size_t>(nb > kMaxRadix ? nb : kMaxRadix) * 4);
     p->off_validcnt = take(static_cast<size_t>(nb) * 4);
     p->off_segstart = take((P + 1) * 4);
     p->off_segidx0 = take(P * 4);
@@ -1045,21 +1200,36 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
 
     // S5: sort pairs by label
     uint32_t *kin = keys0, *kout = keys1, *vin = vals0, *vout = vals1;
-    for (int pass = 0; pass < pl.passes; ++pass) {
-        const int shift = pass * pl.rb;
-        const int radix = 1 << pl.rb;
-        XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts)));
+    if (pl.n_buckets > 0) {
+        // one round on the high digit (masked pairs behind every label), then each bucket by its low digit
+        const int radix = 1 << pl.high_rb;
+        const uint32_t Lk = static_cast<uint32_t>(L);
+        XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, Lk, pl.n_buckets)));
         XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
-        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, 0, st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals)));
+        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, 0, st>>>(kin, vin, kout, vout, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, totals, Lk, pl.n_buckets)));
+        XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, 0, st>>>(kout, vout, kin, vin, totals, pl.low_bits, head_cnt)));
+        // the sizes of the label buckets add up to the number of unmasked pairs
+        XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.n_buckets, 256, 0, st>>>(kin, pl.P, pl.chunk, Lk, pl.n_buckets, head_cnt,
+                                                                                     totals, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
+                                                                                     1.0f / static_cast<float>(B), loss, SQ, totals)));
         XC_HIP_CHECK(hipGetLastError());
-        uint32_t* tk = kin; kin = kout; kout = tk;
-        uint32_t* tv = vin; vin = vout; vout = tv;
+    } else {
+        for (int pass = 0; pass < pl.passes; ++pass) {
+            const int shift = pass * pl.rb;
+            const int radix = 1 << pl.rb;
+            XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, 0xffffffffu, 0)));
+            XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
+            XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, 0, st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals, 0xffffffffu, 0)));
+            XC_HIP_CHECK(hipGetLastError());
+            uint32_t* tk = kin; kin = kout; kout = tk;
+            uint32_t* tv = vin; vin = vout; vout = tv;
+        }
+        XC_LAUNCH(K_HEADS_COUNT, st, (heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt)));
+        XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
+                                                                                valid_cnt, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
+                                                                                1.0f / static_cast<float>(B), loss, SQ, nullptr)));
+        XC_HIP_CHECK(hipGetLastError());
     }
-    XC_LAUNCH(K_HEADS_COUNT, st, (heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt)));
-    XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
-                                                                            valid_cnt, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
-                                                                            1.0f / static_cast<float>(B), loss, SQ)));
-    XC_HIP_CHECK(hipGetLastError());
     if (t == XC_BF16) launch_update<bf16_t>(pl, st, Z, W, d, vin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
     else launch_update<float>(pl, st, Z, W, d, vin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
     XC_HIP_CHECK(hipGetLastError());

@@ -25,6 +25,7 @@ from collections import defaultdict
 KERNELS = {"mine_tile_kernel": "mine_tile", "mine_select_kernel": "mine_select", "mine_init_kernel": "mine_init",
            "sample_kernel": "sample", "gather_kernel": "gather", "radix_count_kernel": "radix_count",
            "radix_prefix_kernel": "radix_scan", "radix_scatter_kernel": "radix_scatter",
+           "bucket_sort_kernel": "bucket_sort",
            "heads_count_kernel": "heads_count", "heads_write_kernel": "heads_write",
            "update_kernel": "update", "copy_probe_kernel": "copy_probe", "mfma_probe_kernel": "mfma_probe"}
 

@@ -133,3 +133,30 @@ def test_step_many_long_segments(dtype):
     out, ref = _run_and_check(Z, W, pos, neg, logq, f64(Z), f64(W), 0.05 if dtype == torch.bfloat16 else 0.3,
                               orc.LOSS_BCE)
     assert len(ref["touched"]) == 64 * n + B
+
+
+@pytest.mark.parametrize("B,L,d,k_p,n_neg,masked", [
+    (96, 8, 64, 2, 640, 0.0),         # 4 label buckets of ~15 000 pairs each: buckets streamed, not held in registers
+    (96, 700, 64, 4, 300, 0.6),       # most pairs masked (-1 / out of range): they bypass the buckets
+    (33, 2, 64, 1, 50, 0.0),          # the smallest label set that takes the bucket path
+    (40, 4_300_000, 64, 3, 200, 0.2),  # more labels than 2047 buckets of 2048: digit-by-digit rounds
+])
+def test_step_sort_paths(B, L, d, k_p, n_neg, masked):
+    """The pair sort behind the row update: bucket sizes far above and below a workgroup's tile,
+    masked pairs, and the wide-key path, all against the oracle (touched ids exact)."""
+    rng = np.random.default_rng(L + B)
+    dtype = torch.float32
+    Z = synth.make_matrix(21, synth.TAG_Z, B, d, dtype, "cuda:0")
+    W = synth.make_matrix(21, synth.TAG_W, L, d, dtype, "cuda:0")
+    pos = rng.integers(0, L, size=(B, k_p)).astype(np.int32)
+    for i in range(B):                                        # distinct positives per query, -1 padded
+        _, first = np.unique(pos[i], return_index=True)
+        dup = np.ones(k_p, bool)
+        dup[first] = False
+        pos[i, dup] = -1
+    neg = rng.integers(0, L, size=(B, n_neg)).astype(np.int32)
+    if masked > 0:
+        m = rng.random((B, n_neg)) < masked
+        neg[m] = np.where(rng.random(int(m.sum())) < 0.5, -1, L + 5).astype(np.int32)
+    logq = np.log(rng.uniform(0.05, 1.0, size=(B, n_neg))).astype(np.float32)
+    _run_and_check(Z, W, pos, neg, logq, f64(Z), f64(W), 0.2, orc.LOSS_BCE)
