@@ -13,12 +13,14 @@
 //       global->LDS loads one stage ahead.  Labels run along the MFMA M axis
 //       and queries along N, so one lane owns one query column and compares its
 //       accumulators with that query's tau; the score matrix never leaves
-//       registers.  Passing scores are parked in a per-wave stash in LDS (slot
-//       from a ballot, no atomic on the path), emptied 64 at a time into a
-//       512-key list per query, and appended to the query's global candidate
-//       list when the workgroup finishes its label slice.  A list that could
-//       overflow is cut to its best k by one wave (radix select) and tau rises
-//       locally: only adversarial score orders get there.
+//       registers.  Passing scores are parked in a per-wave pool in LDS (slot
+//       from a ballot, no atomic on the path) that lives as long as the label
+//       slice; the pool is emptied into a 1024-key list per query when it
+//       fills, and the lists are appended to the queries' global candidate
+//       lists when the workgroup finishes its slice.  The filter of a tile
+//       needs no barrier: the workgroup meets only after a tile in which a
+//       pool was emptied, to cut any list that could overflow to its best k
+//       (radix select by one wave; tau rises locally).
 //   mine_select_kernel  after each phase, one wave per query cuts the global
 //       candidate list to its best k and publishes the new tau; after the last
 //       phase it sorts the winners by (score descending, id ascending).
@@ -33,11 +35,13 @@ constexpr int kBM = 256;            // labels per tile   (MFMA M)
 constexpr int kBN = 256;            // queries per tile  (MFMA N)
 constexpr int kStageBytes = 128;    // bytes of a row staged in LDS per K step (= LDS row pitch; the
                                     // 16-byte chunks of a row are stored swizzled, see lds_chunk_swizzle)
-constexpr int kCandCap = 512;       // keys per query candidate list
-constexpr int kStash = 1024;        // passing scores a wave parks in LDS before it empties them into the lists
+constexpr int kCandCap = 1024;      // keys per query candidate list
+constexpr int kPool = 320;          // passing scores a wave parks in LDS before it empties them into the lists
+constexpr int kPoolCheck = 4;       // accumulators between two looks at the pool's fill (each adds <= 64 entries)
+constexpr int kPoolKeep = kPool - kPoolCheck * 64;      // entries a wave may carry from one tile to the next
 constexpr int kMineThreads = 512;   // 8 waves: 2 along labels x 4 along queries
 constexpr int kMineWaves = kMineThreads / kWave;
-static_assert(kMineWaves * kStash * 8 <= (kBM + kBN) * kStageBytes, "the stashes share one stage buffer");
+static_assert(kPoolKeep >= 0, "the pool holds what can arrive between two looks at its fill");
 constexpr int kMineGrid = 256;      // persistent workgroups, one per compute unit
 constexpr int kXcds = 8;            // workgroup w runs on XCD w % 8
 constexpr int kCusPerXcd = kMineGrid / kXcds;
@@ -194,6 +198,8 @@ __device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_addr /*
 }
 // The same with a wave-uniform 64-bit base and a 32-bit lane offset: no vector arithmetic is needed
 // to form the address, so issuing the load never competes with another wave's MFMAs for the VALU.
+template <int V> using IC = std::integral_constant<int, V>;
+
 template <int kLdsOffset>
 __device__ __forceinline__ void lds_dma16_sbase(const void* sbase /* wave-uniform */, uint32_t voff,
                                                 uint32_t lds_addr /* wave-uniform; kLdsOffset is added */) {
@@ -230,6 +236,8 @@ void mine_tile_kernel(const MineArgs a) {
     float* tau = reinterpret_cast<float*>(smem + 2 * kStageBuf);
     int* cnt = reinterpret_cast<int*>(tau + kBN);
     int* hist = cnt + kBN;                                   // [kMineWaves][256]
+    uint2* pools = reinterpret_cast<uint2*>(hist + kMineWaves * 256);       // [kMineWaves][kPool]
+    int* dirty = reinterpret_cast<int*>(pools + kMineWaves * kPool);        // [2], by tile parity
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) unsigned char*)smem));
 
@@ -241,16 +249,16 @@ void mine_tile_kernel(const MineArgs a) {
     uint64_t* my_lists = a.lists + static_cast<size_t>(blockIdx.x) * kBN * kCandCap;
 
     // ---- which (query tile, label slice) items this workgroup processes
-    int64_t item, item_step, item_end;
+    int item, item_step, item_end;     // (nQT * S fits: at most 2^23 query tiles, 64 slices)
     int slice_fixed = -1;
     if (a.Qx > 0) {                   // slices bound to XCDs: workgroup w runs on XCD w % 8
         const int xcd = blockIdx.x % kXcds;
         const int cu = blockIdx.x / kXcds;
         slice_fixed = xcd + kXcds * (cu / a.Qx);
-        item = cu % a.Qx; item_step = a.Qx; item_end = a.nQT;        // items are query tiles
+        item = cu % a.Qx; item_step = a.Qx; item_end = static_cast<int>(a.nQT);        // items are query tiles
         if (slice_fixed >= a.S) item_end = 0;
     } else {
-        item = blockIdx.x; item_step = kMineGrid; item_end = a.nQT * a.S;
+        item = blockIdx.x; item_step = kMineGrid; item_end = static_cast<int>(a.nQT * a.S);
     }
 
     // ---- fragment reads: lane reads row (lane & 31) of a 32-row block, chunk 2 kk + (lane >> 5);
@@ -279,24 +287,38 @@ void mine_tile_kernel(const MineArgs a) {
         const int64_t qtile = a.Qx > 0 ? item : item / a.S;
         const int slice = a.Qx > 0 ? slice_fixed : static_cast<int>(item % a.S);
         const int64_t t_begin = a.tile_lo + static_cast<int64_t>(slice) * a.tiles_per_slice;
-        int64_t t_end = t_begin + a.tiles_per_slice;
-        t_end = t_end < a.tile_hi ? t_end : a.tile_hi;
-        if (t_end <= t_begin) continue;                      // uniform: an empty slice
+        // tiles of the slice are counted from t_begin in 32 bits (a slice has at most 2^31 / 256 / 8 tiles)
+        int n_tiles;
+        {
+            int64_t t_end = t_begin + a.tiles_per_slice;
+            t_end = t_end < a.tile_hi ? t_end : a.tile_hi;
+            if (t_end <= t_begin) continue;                  // uniform: an empty slice
+            n_tiles = static_cast<int>(t_end - t_begin);
+        }
+        // tiles [0, full_tiles) of the slice have all kBM rows
+        int full_tiles;
+        {
+            const int64_t f = a.L / kBM - t_begin;
+            full_tiles = f < 0 ? 0 : (f < n_tiles ? static_cast<int>(f) : n_tiles);
+        }
         const int64_t q0 = qtile * kBN;
         if (tid < kBN) { tau[tid] = ordered_to_float(a.tau_g[q0 + tid]); cnt[tid] = 0; }
+        if (tid < 2) dirty[tid] = 0;
 
         // ---- the load stream runs one stage ahead of the compute stream and stops at the last stage
         const unsigned char* zbase = a.Z + q0 * a.row_bytes;
-        int64_t ld_tile = t_begin;
+        const unsigned char* wld = a.W + t_begin * kBM * a.row_bytes;       // W rows of the tile being loaded
+        const bool z_full = a.Zq - q0 >= kBN;
+        int ld_tile = 0;
         int ld_kb = 0, ld_slot = 0;
-        int64_t to_issue = (t_end - t_begin) * a.nkb;
+        int to_issue = n_tiles * a.nkb;
         auto issue_stage = [&]() {
-            const int64_t last_row = dma_z ? a.Zq - 1 - q0 : a.L - 1 - ld_tile * kBM;
-            const unsigned char* base = dma_z ? zbase : a.W + ld_tile * kBM * a.row_bytes;
+            const bool full = dma_z ? z_full : ld_tile < full_tiles;
+            const unsigned char* base = dma_z ? zbase : wld;
             const uint32_t kb = static_cast<uint32_t>(ld_kb) * kStageBytes;
             const uint32_t dst = dma_dst + static_cast<uint32_t>(ld_slot) * kStageBuf;
             if ((wave < 4) == (ld_slot == 0)) {              // this half's turn
-                if (!KTAIL && last_row >= kBM - 1) {
+                if (!KTAIL && full) {
                     // the usual case: every row of the tile exists.  Lane offsets voff[t & 1] are the
                     // same for all stages; everything else is added to the scalar base.
                     const uint64_t b64 = reinterpret_cast<uint64_t>(base + kb);     // wave-uniform
@@ -318,12 +340,13 @@ void mine_tile_kernel(const MineArgs a) {
                     pair(std::integral_constant<int, 8>{});  pair(std::integral_constant<int, 10>{});
                     pair(std::integral_constant<int, 12>{}); pair(std::integral_constant<int, 14>{});
                 } else {
+                    const int64_t last_row = dma_z ? a.Zq - 1 - q0 : a.L - 1 - (t_begin + ld_tile) * kBM;
                     issue_stage_slow<KTAIL>(base, last_row, a.row_bytes, kb, drow, dcol[0], dcol[1], dst, a.zeros);
                 }
             }
             ld_slot ^= 1;
             --to_issue;
-            if (++ld_kb == a.nkb) { ld_kb = 0; ++ld_tile; }
+            if (++ld_kb == a.nkb) { ld_kb = 0; ++ld_tile; wld += kBM * a.row_bytes; }
         };
 
         f32x16 acc[4][2];
@@ -367,7 +390,45 @@ void mine_tile_kernel(const MineArgs a) {
         issue_stage();
         publish_next(smem);                                  // stage 0 visible, stage 1 under way
 
-        for (int64_t tile = t_begin; tile < t_end; ++tile) {
+        // ---- a passing score is first parked, with its query and label offset, in this wave's pool:
+        // the slot comes from a ballot and a wave-uniform fill count, so nothing waits on an atomic.
+        // The pool is emptied into the per-query lists (slots from LDS counters) when it fills up, at
+        // the end of a tile if it holds more than kPoolKeep entries, and at the end of the slice.
+        // No barrier is needed for any of that; what does need the whole workgroup - cutting a list
+        // that could overflow, closing the slice - is done at the start of the next tile's filter,
+        // when a flag says that lists have grown.
+        uint2* pool = pools + wave * kPool;
+        int fill = 0;
+        int pool_tile = 0;                                   // labels in the pool count from this tile
+        auto flush = [&]() {
+            const int64_t l0 = (t_begin + pool_tile) * kBM;
+#pragma unroll 1
+            for (int e0 = 0; e0 < fill; e0 += 2 * kWave) {   // two batches of 64 at a time: the slot atomics overlap
+                uint2 en[2];
+                int slot[2];
+                bool ok[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int e = e0 + u * kWave + lane;
+                    ok[u] = e < fill;
+                    en[u] = ok[u] ? pool[e] : make_uint2(0u, 0u);
+                    ok[u] = ok[u] && (l0 + (en[u].y & 0xffffffu) < a.L);   // rows past the end repeat the last row
+                }
+#pragma unroll
+                for (int u = 0; u < 2; ++u) slot[u] = ok[u] ? atomicAdd(&cnt[en[u].y >> 24], 1) : 0;
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    if (ok[u])
+                        my_lists[static_cast<size_t>(en[u].y >> 24) * kCandCap + slot[u]] =
+                            make_key(__uint_as_float(en[u].x) + 0.0f /* -0 -> +0 */,
+                                     static_cast<int32_t>(l0 + (en[u].y & 0xffffffu)));
+                }
+            }
+            fill = 0;
+        };
+
+        for (int tile = 0; tile < n_tiles; ++tile) {          // counted from t_begin
+            const int par = tile & 1;
             for (int kb = 0; kb < a.nkb; ++kb) {
                 const unsigned char* cur = smem + buf_sel * kStageBuf;
                 const unsigned char* nxt = smem + (buf_sel ^ 1) * kStageBuf;
@@ -384,52 +445,18 @@ void mine_tile_kernel(const MineArgs a) {
                 __builtin_amdgcn_sched_barrier(0);
                 products(0);
                 __builtin_amdgcn_sched_barrier(0);
-                if (kb + 1 < a.nkb) publish_next(nxt);       // within a tile: before the last products
+                // the next stage - of this tile or of the next one - is published before the last products
+                if (kb + 1 < a.nkb || tile + 1 < n_tiles) publish_next(nxt);
                 __builtin_amdgcn_sched_barrier(0);
                 products(1);
                 __builtin_amdgcn_sched_barrier(0);
             }
 
-            // ---- threshold filter: lane owns query column (lane & 31) of each N tile.  A score that
-            // passes is first parked, with its query and row, in this wave's stash: the slot comes
-            // from a ballot and a wave-uniform fill count, so nothing waits on an atomic.  The stash
-            // lives in the stage buffer that was read last (no load is in flight into it until the
-            // next tile's second stage) and is emptied 64 entries at a time into the per-query lists.
-            __syncthreads();                                 // every wave has finished reading that buffer
-            uint2* stash = reinterpret_cast<uint2*>(smem + (buf_sel ^ 1) * kStageBuf) + wave * kStash;
-            const int64_t l0 = tile * kBM;
-            int fill = 0;
-            auto flush = [&]() {
-                // four batches of 64 entries at a time, so that the slot atomics overlap
-                for (int e0 = 0; e0 < fill; e0 += 4 * kWave) {
-                    uint2 en[4];
-                    int slot[4];
-                    bool ok[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int e = e0 + u * kWave + lane;
-                        ok[u] = e < fill;
-                        en[u] = ok[u] ? stash[e] : make_uint2(0u, 0u);
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        if (e0 + u * kWave >= fill) break;                     // uniform
-                        ok[u] = ok[u] && (l0 + (en[u].y & 255u) < a.L);      // rows past the end repeat the last row
-                        slot[u] = ok[u] ? atomicAdd(&cnt[en[u].y >> 8], 1) : 0;
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        if (e0 + u * kWave >= fill) break;
-                        if (ok[u])
-                            my_lists[static_cast<size_t>(en[u].y >> 8) * kCandCap + slot[u]] =
-                                make_key(__uint_as_float(en[u].x) + 0.0f /* -0 -> +0 */,
-                                         static_cast<int32_t>(l0 + (en[u].y & 255u)));
-                    }
-                }
-                fill = 0;
-            };
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) {
+
+            // ---- threshold filter: lane owns query column (lane & 31) of each N tile
+            bool grew = false;                               // this wave emptied its pool during the tile
+            auto filter = [&](auto ntc) {
+                constexpr int nt = decltype(ntc)::value;
                 const int qloc = wn * 64 + nt * 32 + (lane & 31);
                 const float t = (q0 + qloc) < a.Zq ? tau[qloc] : INFINITY;
                 float mx = acc[0][nt][0];
@@ -438,28 +465,43 @@ void mine_tile_kernel(const MineArgs a) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[mt][nt][i]);
                 if (__ballot(mx >= t) != 0ull) {
-                    uint32_t qrow = static_cast<uint32_t>((qloc << 8) | (4 * (lane >> 5)));
-                    asm volatile("" : "+v"(qrow));           // keep the 64 row words out of registers
+                    // entry: score bits, query << 24 | label offset from the pool's first tile
+                    auto row_word = [&]() {
+                        uint32_t w = (static_cast<uint32_t>(qloc) << 24) |
+                                     (static_cast<uint32_t>(tile - pool_tile) * kBM + static_cast<uint32_t>(4 * (lane >> 5)));
+                        asm volatile("" : "+v"(w));          // keep the 64 row words out of registers
+                        return w;
+                    };
+                    uint32_t qrow = row_word();
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const float v = acc[mt][nt][i];
-                            const bool hit = v >= t;
-                            const uint64_t m = __ballot(hit);
-                            if (__builtin_expect(m != 0ull, 0)) {        // out of line: a taken branch costs more
-                                if (hit) {
-                                    const int pos = fill + static_cast<int>(__builtin_amdgcn_mbcnt_hi(
-                                        static_cast<uint32_t>(m >> 32),
-                                        __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u)));
-                                    stash[pos] = make_uint2(
-                                        __float_as_uint(v),
-                                        qrow + static_cast<uint32_t>(wm * 128 + mt * 32 + 8 * (i >> 2) + (i & 3)));
+                        for (int i0 = 0; i0 < 16; i0 += kPoolCheck) {
+#pragma unroll
+                            for (int ii = 0; ii < kPoolCheck; ++ii) {
+                                const int i = i0 + ii;
+                                const float v = acc[mt][nt][i];
+                                const bool hit = v >= t;
+                                const uint64_t m = __ballot(hit);
+                                if (__builtin_expect(m != 0ull, 0)) {    // out of line: a taken branch costs more
+                                    if (hit) {
+                                        const int pos = fill + static_cast<int>(__builtin_amdgcn_mbcnt_hi(
+                                            static_cast<uint32_t>(m >> 32),
+                                            __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u)));
+                                        pool[pos] = make_uint2(
+                                            __float_as_uint(v),
+                                            qrow + static_cast<uint32_t>(wm * 128 + mt * 32 + 8 * (i >> 2) + (i & 3)));
+                                    }
+                                    fill += __popcll(m);
                                 }
-                                fill += __popcll(m);
                             }
-                            // 8 values add at most 512 entries
-                            if ((i & 7) == 7 && fill > kStash - 8 * kWave) flush();
+                            // kPoolCheck accumulators add at most kPool - kPoolKeep entries
+                            if (__builtin_expect(fill > kPoolKeep, 0)) {
+                                flush();
+                                pool_tile = tile;
+                                qrow = row_word();
+                                grew = true;
+                            }
                         }
                     }
                 }
@@ -467,19 +509,31 @@ void mine_tile_kernel(const MineArgs a) {
                 for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.0f;
+            };
+            filter(IC<0>{});
+            filter(IC<1>{});
+            // the label offset of an entry has 24 bits
+            if (fill > 0 && (tile + 1 == n_tiles || tile - pool_tile >= 60000)) {
+                flush();
+                pool_tile = tile;
+                grew = true;
             }
-            if (fill > 0) flush();
-            __syncthreads();
+            if (grew && lane == 0) dirty[par] = 1;
 
-            // ---- wave w looks after queries 32w..32w+31.  A list that could overflow during the
-            // next tile (or, at the end of the slice, exceeds what a slice may append) is cut to
-            // its best k and tau rises for the rest of the slice.
-            {
-                const bool last = (tile + 1 == t_end);
+            // ---- lists grown during the previous tile (the flag was set before barriers that every
+            // wave has passed since), or the end of the slice: wave w looks after queries 32w..32w+31.
+            // A list that could overflow before the next look (two tiles add at most 2 kBM entries, the
+            // two pools that feed it at most kPoolKeep each), or, at the end of the slice, exceeds what
+            // a slice may append, is cut to its best k and tau rises for the rest of the slice.
+            const bool last = tile + 1 == n_tiles;
+            if (last) __syncthreads();                       // (a one-stage tile has no barrier of its own)
+            if (last || dirty[par ^ 1] != 0) {               // uniform
+                __syncthreads();                             // the pools' stores to the lists are complete
                 const int qloc = wave * 32 + (lane & 31);
                 const bool qok = (q0 + qloc) < a.Zq;
                 int n = cnt[qloc];
-                const bool want = lane < 32 && qok && (last ? n > a.append_max : n > kCandCap - kBM);
+                const bool want = lane < 32 && qok &&
+                                  (last ? n > a.append_max : n > kCandCap - 2 * kBM - 2 * kPoolKeep);
                 uint64_t todo = __ballot(want);
                 if (todo != 0ull || last) {
                     float t_new = -INFINITY;
@@ -545,11 +599,9 @@ void mine_tile_kernel(const MineArgs a) {
                         }
                     }
                 }
+                if (tid == 0) { dirty[par ^ 1] = 0; if (last) dirty[par] = 0; }
+                __syncthreads();
             }
-            __syncthreads();
-            // the stash is done with: the next tile's first stage (its loads went out during this
-            // tile's last stage) is published now
-            if (tile + 1 < t_end) publish_next(smem + buf_sel * kStageBuf);
         }
     }
 }
@@ -737,7 +789,8 @@ static int plan_mine(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, MinePlan
     p->off_tau = take(nq * sizeof(uint32_t));
     p->off_zero = take(256);
     p->ws_bytes = off;
-    p->lds_tile = 2 * static_cast<size_t>(kBM + kBN) * kStageBytes + kBN * 8 + kMineWaves * 256 * 4;
+    p->lds_tile = 2 * static_cast<size_t>(kBM + kBN) * kStageBytes + kBN * 8 + kMineWaves * 256 * 4 +
+                  static_cast<size_t>(kMineWaves) * kPool * 8 + 16;
     return XC_OK;
 }
 
