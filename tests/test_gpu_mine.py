@@ -51,10 +51,12 @@ def test_mine_long_slices_exercise_list_reduction():
     _case(5, 512, 131072, 64, torch.bfloat16, 64)
 
 
-def test_mine_increasing_scores_worst_case_for_the_threshold():
-    # score(i, l) grows with l: every label beats the running threshold
+@pytest.mark.parametrize("L,Zq,k", [(40000, 140, 33), (300000, 260, 128)])
+def test_mine_increasing_scores_worst_case_for_the_threshold(L, Zq, k):
+    # score(i, l) grows with l: every label beats the running threshold, in every phase, so every
+    # accumulator is parked, the pools are emptied all the time and the lists are cut after every tile
     dev = "cuda:0"
-    L, d, Zq, k = 40000, 16, 140, 33
+    d = 16
     base = torch.ones(d, dtype=torch.float32)
     W = (torch.arange(L, dtype=torch.float32)[:, None] / 65536.0 * base[None, :]).to(torch.bfloat16).to(dev)
     Z = torch.ones((Zq, d), dtype=torch.bfloat16, device=dev)
