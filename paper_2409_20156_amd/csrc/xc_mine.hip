@@ -274,7 +274,6 @@ void mine_tile_kernel(const MineArgs a) {
     // w & 3 = 0 / 1, Z rows likewise for 2 / 3; instruction t covers rows 8 t .. 8 t + 7 of them,
     // lane i -> row i / 8, position i % 8.  The chunk a lane fetches is position ^ swizzle(row),
     // which depends on t only through t & 1.
-    constexpr int kDmaInstr = 16;
     const bool dma_z = (wave & 3) >= 2;
     const int drow = (wave & 1) * 128 + (lane >> 3);
     const uint32_t dcol[2] = {static_cast<uint32_t>(((lane & 7) ^ (lane >> 4)) * 16),

@@ -651,7 +651,7 @@ void heads_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
     sh[0][threadIdx.x] = h; sh[1][threadIdx.x] = v;
     __syncthreads();
     for (int s = 128; s > 0; s >>= 1) {
-        if (threadIdx.x < s) { sh[0][threadIdx.x] += sh[0][threadIdx.x + s]; sh[1][threadIdx.x] += sh[1][threadIdx.x + s]; }
+        if (static_cast<int>(threadIdx.x) < s) { sh[0][threadIdx.x] += sh[0][threadIdx.x + s]; sh[1][threadIdx.x] += sh[1][threadIdx.x + s]; }
         __syncthreads();
     }
     if (threadIdx.x == 0) { head_cnt[blockIdx.x] = sh[0][0]; valid_cnt[blockIdx.x] = sh[1][0]; }
