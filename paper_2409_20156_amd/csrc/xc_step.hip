@@ -13,7 +13,8 @@ namespace xc {
 constexpr int kStepThreads = 256;
 constexpr int kMaxRowFloats = XC_MAX_ROW_BYTES / 2;     // bf16 rows hold the most elements
 constexpr int kSortTile = 256;                          // keys ranked together in the scatter
-constexpr int kSortMaxBlocks = 512;
+constexpr int kSortMaxBlocks = 2048;
+constexpr int kSortCountEntries = 1 << 19;              // digit values x sort blocks at most (2 MiB of counts)
 constexpr int kUpdateMaxGrid = 256 * 8;                 // workgroups of the update kernel
 constexpr int kMaxRadixBits = 11;
 constexpr int kMaxRadix = 1 << kMaxRadixBits;
@@ -446,10 +447,11 @@ void radix_prefix_kernel(int* __restrict__ counts /* [radix][nb], in place */, i
 // One tile of kSortTile keys: key/val of thread tid (valid or not) goes to offs[digit] + its rank among
 // the tile's keys of the same digit, and offs moves on.  whist must be zero on entry and is zero on exit.
 __device__ __forceinline__ void place_tile(bool valid, uint32_t key, uint32_t val, int digit, int rb,
-                                           int* offs, int (*whist)[kMaxRadix],
+                                           int* offs /* [radix] */, int* whist /* [waves][radix] */,
                                            uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out) {
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
+    const int radix = 1 << rb;
     // lanes of this wave holding the same digit
     uint64_t same = __ballot(valid);
     for (int b = 0; b < rb; ++b) {
@@ -458,11 +460,11 @@ __device__ __forceinline__ void place_tile(bool valid, uint32_t key, uint32_t va
         same &= bit ? bal : ~bal;
     }
     const int rank = __popcll(same & lanemask_lt());
-    if (valid && rank == 0) whist[wave][digit] = __popcll(same);
+    if (valid && rank == 0) whist[wave * radix + digit] = __popcll(same);
     __syncthreads();
     if (valid) {
         int before = offs[digit];
-        for (int w = 0; w < wave; ++w) before += whist[w][digit];
+        for (int w = 0; w < wave; ++w) before += whist[w * radix + digit];
         keys_out[before + rank] = key;
         vals_out[before + rank] = val;
     }
@@ -471,15 +473,15 @@ __device__ __forceinline__ void place_tile(bool valid, uint32_t key, uint32_t va
     if (valid && rank == 0) {
         int add = 0;
 #pragma unroll
-        for (int w = 0; w < kSortTile / kWave; ++w) add += whist[w][digit];
+        for (int w = 0; w < kSortTile / kWave; ++w) add += whist[w * radix + digit];
         // one lane per (wave, digit); the wave holding the lowest index among the waves
         // that saw the digit applies the update
         bool first = true;
-        for (int w = 0; w < wave; ++w) first = first && whist[w][digit] == 0;
+        for (int w = 0; w < wave; ++w) first = first && whist[w * radix + digit] == 0;
         if (first) offs[digit] += add;
     }
     __syncthreads();
-    if (valid && rank == 0) whist[wave][digit] = 0;
+    if (valid && rank == 0) whist[wave * radix + digit] = 0;
     __syncthreads();
 }
 
@@ -488,12 +490,13 @@ void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* 
                           uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, int64_t P,
                           int64_t chunk, int shift, int rb, int nb, const int* __restrict__ prefix,
                           const int* __restrict__ totals, uint32_t inv_key, int inv_digit) {
-    __shared__ int offs[kMaxRadix];
-    __shared__ int whist[kSortTile / kWave][kMaxRadix];
+    extern __shared__ int sort_lds[];                  // offs[radix], whist[waves][radix]: sized by the launch
     __shared__ int wsum[kSortTile / kWave];
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int radix = 1 << rb;
+    int* offs = sort_lds;
+    int* whist = sort_lds + radix;
     const int per = (radix + kSortTile - 1) / kSortTile;     // digits per thread, contiguous
     // digit bases: exclusive scan of the totals
     {
@@ -511,7 +514,7 @@ void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* 
     }
     for (int d = tid; d < radix; d += kSortTile)
 #pragma unroll
-        for (int w = 0; w < kSortTile / kWave; ++w) whist[w][d] = 0;
+        for (int w = 0; w < kSortTile / kWave; ++w) whist[w * radix + d] = 0;
     __syncthreads();
     const int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
@@ -540,13 +543,14 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
                         uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out,
                         const int* __restrict__ sizes /* [gridDim.x] pairs per bucket */, int rb,
                         int* __restrict__ head_cnt /* [gridDim.x] */) {
-    __shared__ int offs[kMaxRadix];
-    __shared__ int whist[kSortTile / kWave][kMaxRadix];
+    extern __shared__ int sort_lds[];                  // offs[radix], whist[waves][radix]: sized by the launch
     __shared__ int wsum[kSortTile / kWave];
     __shared__ int red[kSortTile];
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int radix = 1 << rb;
+    int* offs = sort_lds;
+    int* whist = sort_lds + radix;
     const int b = blockIdx.x;
     {   // where the bucket starts: the sizes of the buckets before it
         int t = 0;
@@ -556,7 +560,7 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
     for (int d = tid; d < radix; d += kSortTile) {
         offs[d] = 0;
 #pragma unroll
-        for (int w = 0; w < kSortTile / kWave; ++w) whist[w][d] = 0;
+        for (int w = 0; w < kSortTile / kWave; ++w) whist[w * radix + d] = 0;
     }
     __syncthreads();
     for (int s2 = kSortTile / 2; s2 > 0; s2 >>= 1) {
@@ -998,6 +1002,9 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
+static size_t sort_lds_bytes(int rb) {      // offs + one histogram per wave, for digits of rb bits
+    return (static_cast<size_t>(1) + kSortTile / kWave) * (static_cast<size_t>(1) << rb) * sizeof(int);
+}
 struct StepPlan {
     int64_t P;
     int n, G, cpl, nb, passes, rb, key_bits, sq, n_shift;
@@ -1032,14 +1039,6 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     p->G = G;
     p->cpl = (nchunks + G - 1) / G;
     if (p->cpl > 4) return XC_ESHAPE;
-    int nb = static_cast<int>((p->P + 511) / 512);        // two 256-key tiles per block at least
-    if (nb > kSortMaxBlocks) nb = kSortMaxBlocks;
-    if (nb < 1) nb = 1;
-    int64_t chunk = (p->P + nb - 1) / nb;
-    chunk = (chunk + kSortTile - 1) / kSortTile * kSortTile;
-    nb = static_cast<int>((p->P + chunk - 1) / chunk);
-    p->nb = nb;
-    p->chunk = chunk;
     int bits = 1;
     if (L >= 0) { while ((static_cast<int64_t>(1) << bits) <= L && bits < 32) ++bits; }
     p->key_bits = bits;                                // keys take values 0..L
@@ -1062,6 +1061,19 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
             p->high_rb = hb;
         }
     }
+    // blocks of the sort: two 256-key tiles per block at least; the [digit][block] count matrix, which is
+    // written and read across its rows, stays within kSortCountEntries
+    const int radix_max = 1 << (p->n_buckets > 0 ? p->high_rb : p->rb);
+    int nb_cap = kSortCountEntries / radix_max;
+    if (nb_cap > kSortMaxBlocks) nb_cap = kSortMaxBlocks;
+    int nb = static_cast<int>((p->P + 511) / 512);
+    if (nb > nb_cap) nb = nb_cap;
+    if (nb < 1) nb = 1;
+    int64_t chunk = (p->P + nb - 1) / nb;
+    chunk = (chunk + kSortTile - 1) / kSortTile * kSortTile;
+    nb = static_cast<int>((p->P + chunk - 1) / chunk);
+    p->nb = nb;
+    p->chunk = chunk;
     size_t off = 0;
     auto take = [&off](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
     const size_t P = static_cast<size_t>(p->P);
@@ -1072,10 +1084,10 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     p->sq = B >= 1536 ? 1 : (B >= 768 ? 2 : 4);
     p->off_lossq = take(static_cast<size_t>(B) * p->sq * 4);
     p->off_dzpart = take(p->sq > 1 ? static_cast<size_t>(B) * p->sq * d * 4 : 0);
-    p->off_counts = take(static_cast<size_t>(kMaxRadix) * nb * 4);
+    p->off_counts = take(static_cast<size_t>(kSortCountEntries) * 4);      // whatever L: the layout does not depend on it
     p->off_totals = take(static_cast<size_t>(kMaxRadix) * 4);
-    p->off_headcnt = take(static_cast<size_t>(nb > kMaxRadix ? nb : kMaxRadix) * 4);
-    p->off_validcnt = take(static_cast<size_t>(nb) * 4);
+    p->off_headcnt = take(static_cast<size_t>(kSortMaxBlocks > kMaxRadix ? kSortMaxBlocks : kMaxRadix) * 4);
+    p->off_validcnt = take(static_cast<size_t>(kSortMaxBlocks) * 4);
     p->off_segstart = take((P + 1) * 4);
     p->off_segidx0 = take(P * 4);
     p->total = off;
@@ -1206,8 +1218,8 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
         const uint32_t Lk = static_cast<uint32_t>(L);
         XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, Lk, pl.n_buckets)));
         XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
-        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, 0, st>>>(kin, vin, kout, vout, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, totals, Lk, pl.n_buckets)));
-        XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, 0, st>>>(kout, vout, kin, vin, totals, pl.low_bits, head_cnt)));
+        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.high_rb), st>>>(kin, vin, kout, vout, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, totals, Lk, pl.n_buckets)));
+        XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, sort_lds_bytes(pl.low_bits), st>>>(kout, vout, kin, vin, totals, pl.low_bits, head_cnt)));
         // the sizes of the label buckets add up to the number of unmasked pairs
         XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.n_buckets, 256, 0, st>>>(kin, pl.P, pl.chunk, Lk, pl.n_buckets, head_cnt,
                                                                                      totals, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
@@ -1219,7 +1231,7 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
             const int radix = 1 << pl.rb;
             XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, 0xffffffffu, 0)));
             XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
-            XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, 0, st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals, 0xffffffffu, 0)));
+            XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.rb), st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals, 0xffffffffu, 0)));
             XC_HIP_CHECK(hipGetLastError());
             uint32_t* tk = kin; kin = kout; kout = tk;
             uint32_t* tv = vin; vin = vout; vout = tv;
