@@ -461,14 +461,14 @@ __device__ __forceinline__ void place_tile(bool valid, uint32_t key, uint32_t va
     }
     const int rank = __popcll(same & lanemask_lt());
     if (valid && rank == 0) whist[wave * radix + digit] = __popcll(same);
-    __syncthreads();
+    lds_barrier();
     if (valid) {
         int before = offs[digit];
         for (int w = 0; w < wave; ++w) before += whist[w * radix + digit];
         keys_out[before + rank] = key;
         vals_out[before + rank] = val;
     }
-    __syncthreads();
+    lds_barrier();
     // only digits present in this tile need their running offset advanced
     if (valid && rank == 0) {
         int add = 0;
@@ -480,9 +480,9 @@ __device__ __forceinline__ void place_tile(bool valid, uint32_t key, uint32_t va
         for (int w = 0; w < wave; ++w) first = first && whist[w * radix + digit] == 0;
         if (first) offs[digit] += add;
     }
-    __syncthreads();
+    lds_barrier();
     if (valid && rank == 0) whist[wave * radix + digit] = 0;
-    __syncthreads();
+    lds_barrier();
 }
 
 __global__ __launch_bounds__(kSortTile)
@@ -519,11 +519,14 @@ void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* 
     const int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
     p1 = p1 < P ? p1 : P;
+    // the next tile's pairs are fetched while the current tile is placed
+    uint32_t key_n = 0, val_n = 0;
+    if (p0 + tid < p1) { key_n = keys_in[p0 + tid]; val_n = vals_in[p0 + tid]; }
     for (int64_t t0 = p0; t0 < p1; t0 += kSortTile) {
-        const int64_t p = t0 + tid;
-        const bool valid = p < p1;
-        uint32_t key = 0, val = 0;
-        if (valid) { key = keys_in[p]; val = vals_in[p]; }
+        const bool valid = t0 + tid < p1;
+        const uint32_t key = key_n, val = val_n;
+        const int64_t pn = t0 + kSortTile + tid;
+        if (pn < p1) { key_n = keys_in[pn]; val_n = vals_in[pn]; }
         place_tile(valid, key, val, digit_of(key, shift, radix, inv_key, inv_digit), rb, offs, whist, keys_out, vals_out);
     }
 }
@@ -621,11 +624,13 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
                        keys_out, vals_out);
         }
     } else {
+        uint32_t key_n = 0, val_n = 0;
+        if (p0 + tid < p1) { key_n = keys_in[p0 + tid]; val_n = vals_in[p0 + tid]; }
         for (int t0 = p0; t0 < p1; t0 += kSortTile) {
-            const int p = t0 + tid;
-            const bool valid = p < p1;
-            uint32_t key = 0, val = 0;
-            if (valid) { key = keys_in[p]; val = vals_in[p]; }
+            const bool valid = t0 + tid < p1;
+            const uint32_t key = key_n, val = val_n;
+            const int pn = t0 + kSortTile + tid;
+            if (pn < p1) { key_n = keys_in[pn]; val_n = vals_in[pn]; }
             place_tile(valid, key, val, static_cast<int>(key & static_cast<uint32_t>(radix - 1)), rb, offs, whist,
                        keys_out, vals_out);
         }
@@ -729,7 +734,7 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
         const bool head = p < p1 && is_head(keys, p, Lkey);
         const uint64_t bal = __ballot(head);
         if ((tid & 63) == 0) wcnt[tid >> 6] = __popcll(bal);
-        __syncthreads();
+        lds_barrier();
         int before = running;
         for (int w = 0; w < (tid >> 6); ++w) before += wcnt[w];
         if (head) {
@@ -738,9 +743,9 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
             seg_start[s] = static_cast<int32_t>(p);
             seg_idx0[s] = vals[p];               // first pair of the segment, saves the update a hop
         }
-        __syncthreads();
+        lds_barrier();
         if (tid == 0) running += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
-        __syncthreads();
+        lds_barrier();
     }
 }
 
