@@ -36,6 +36,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", help="tiny, c2, c3, c4 or c5")
     ap.add_argument("--pool", type=int, default=0, help="override the mined query pool size")
+    ap.add_argument("--warm-margin", type=float, default=0.1,
+                    help="refreshes after the first start from the thresholds of the one before, lowered by this "
+                         "relative margin (xc_mine_negatives_warm: same shortlists); negative: every refresh is a full search")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -49,7 +52,7 @@ def parse_args():
 class Job:
     """Device-resident state of one workload and the step function."""
 
-    def __init__(self, wl, pool, device="cuda:0"):
+    def __init__(self, wl, pool, device="cuda:0", warm_margin=None):
         import numpy as np
         import torch
 
@@ -80,9 +83,15 @@ class Job:
         self.valid_pairs = [int((pos[b * wl.B:(b + 1) * wl.B] >= 0).sum()) + wl.B * n_neg
                             for b in range(self.nbatch)]
         self.t = 0
+        self.mined = False
+        self.warm_margin = warm_margin
 
     def mine(self):
-        self.xc.mine_negatives(self.Zpool, self.W, self.wl.k_h, workspace=self.mine_ws, out=self.shortlist)
+        # every refresh after the first starts from the thresholds of the one before (same result)
+        margin = self.warm_margin if self.mined else None
+        self.xc.mine_negatives(self.Zpool, self.W, self.wl.k_h, workspace=self.mine_ws, out=self.shortlist,
+                               warm_margin=margin)
+        self.mined = True
 
     def step(self):
         wl, t = self.wl, self.t
@@ -147,7 +156,7 @@ def main():
     xc.load_library()
     wl = synth.WORKLOADS[args.workload]
     pool = args.pool or wl.pool
-    job = Job(wl, pool)
+    job = Job(wl, pool, warm_margin=args.warm_margin if args.warm_margin >= 0 else None)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -238,7 +247,9 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": "%s: L=%d d=%d %s B=%d k_p<=%d k_h=%d k_r=%d pool=%d refresh=%d"
                                % (wl.name, wl.L, wl.d, wl.dtype, wl.B, wl.k_p, wl.k_h, wl.k_r, pool, wl.refresh),
-                   "loss": "bce"},
+                   "loss": "bce",
+                   "refresh_search": ("exact, warm start from the previous thresholds (margin %g)" % args.warm_margin)
+                                     if args.warm_margin >= 0 else "exact, full search every time"},
         "roofline": roofline,
         "kernels_us": {n: round(k["avg_us"], 2) for n, k in kernels.items()},
     }

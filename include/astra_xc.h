@@ -69,6 +69,21 @@ int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64_t L, int d
                       float* scores /* [Zq*k_h] out, or NULL */,
                       void* ws, size_t ws_bytes, void* stream);
 
+/* The same search, with the same result in every case, started from the thresholds that the previous
+ * search with this workspace left in it: Alg. 1 repeats the search every tau_r steps on a classifier that
+ * has moved little, so the k_h-th score of a query, lowered by rel_margin * |score|, is a threshold
+ * that its new k_h best labels almost always pass.  One sweep over the labels with these thresholds
+ * and one selection replace the phased search.  If a query comes out of the sweep with fewer than
+ * k_h candidates (the classifier moved further than the margin, or the workspace held nothing
+ * useful), a flag is raised on the device for its tile of 256 queries and the call repeats the full
+ * search for the flagged tiles; whatever the workspace holds, the result is exact and only the time
+ * differs.  rel_margin >= 0.  The first 32-bit word of the workspace is 1 after the call if some tile
+ * needed the full search, else 0 (device memory; read it after synchronising the stream). */
+int xc_mine_negatives_warm(const void* Z, const void* W, int64_t Zq, int64_t L, int d, int k_h,
+                           xc_dtype t, float rel_margin, int32_t* shortlist /* [Zq*k_h] out */,
+                           float* scores /* [Zq*k_h] out, or NULL */,
+                           void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------
  * Negative sampling (Alg. 1, hard+random step; Sec. 3.1 Idea 2; p under Eq. 2).
  * For query i of the batch, neg[i*(k_h+k_r) + ...]:

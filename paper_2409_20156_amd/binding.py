@@ -27,6 +27,8 @@ _SIGNATURES = {
     "xc_mine_workspace": (_i32, [_i64, _i64, _i32, _i32, _i32, _szp]),
     "xc_mine_negatives": (_i32, [_ptr, _ptr, _i64, _i64, _i32, _i32, _i32, _ptr, _ptr, _ptr,
                                  ctypes.c_size_t, _ptr]),
+    "xc_mine_negatives_warm": (_i32, [_ptr, _ptr, _i64, _i64, _i32, _i32, _i32, ctypes.c_float, _ptr, _ptr, _ptr,
+                                      ctypes.c_size_t, _ptr]),
     "xc_sample_negatives": (_i32, [_ptr, _i64, _i32, _i32, _i64, _u64, _ptr, _ptr, _ptr]),
     "xc_sample_negatives_mixture": (_i32, [ctypes.c_void_p, ctypes.c_void_p, _i64, _i32, _i32, _i32, _i64,
                                            ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
@@ -108,8 +110,13 @@ def mine_workspace(Zq: int, L: int, d: int, k_h: int, dtype_code: int) -> int:
 
 
 def mine_negatives(Z: torch.Tensor, W: torch.Tensor, k_h: int, *, want_scores: bool = False,
-                   workspace: torch.Tensor | None = None, out: torch.Tensor | None = None):
-    """shortlist int32 [Zq, k_h] (and fp32 scores if asked): exact top-k_h of Z W^T per row."""
+                   workspace: torch.Tensor | None = None, out: torch.Tensor | None = None,
+                   warm_margin: float | None = None):
+    """shortlist int32 [Zq, k_h] (and fp32 scores if asked): exact top-k_h of Z W^T per row.
+
+    warm_margin (relative, >= 0): start from the thresholds the previous search left in `workspace`
+    (same result, usually less time); `workspace[:4]` viewed as int32 is 1 afterwards if the full
+    search had to be repeated."""
     lib = load_library()
     code = _dtype_code(Z)
     if W.dtype != Z.dtype or Z.dim() != 2 or W.dim() != 2 or Z.shape[1] != W.shape[1]:
@@ -122,11 +129,18 @@ def mine_negatives(Z: torch.Tensor, W: torch.Tensor, k_h: int, *, want_scores: b
     if out is None:
         out = torch.empty((Zq, k_h), dtype=torch.int32, device=Z.device)
     scores = torch.empty((Zq, k_h), dtype=torch.float32, device=Z.device) if want_scores else None
-    _check(lib.xc_mine_negatives(_dev(Z, name="Z"), _dev(W, name="W"), Zq, L, d, k_h, code,
-                                 _dev(out, torch.int32, "shortlist"),
-                                 _dev(scores, torch.float32, "scores") if want_scores else None,
-                                 _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
-           "xc_mine_negatives")
+    if warm_margin is None:
+        _check(lib.xc_mine_negatives(_dev(Z, name="Z"), _dev(W, name="W"), Zq, L, d, k_h, code,
+                                     _dev(out, torch.int32, "shortlist"),
+                                     _dev(scores, torch.float32, "scores") if want_scores else None,
+                                     _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
+               "xc_mine_negatives")
+    else:
+        _check(lib.xc_mine_negatives_warm(_dev(Z, name="Z"), _dev(W, name="W"), Zq, L, d, k_h, code,
+                                          float(warm_margin), _dev(out, torch.int32, "shortlist"),
+                                          _dev(scores, torch.float32, "scores") if want_scores else None,
+                                          _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
+               "xc_mine_negatives_warm")
     return (out, scores) if want_scores else out
 
 

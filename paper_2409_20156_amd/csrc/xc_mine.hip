@@ -180,6 +180,8 @@ struct MineArgs {
     int32_t* gcnt;           // [nQT*kBN] fill of glist
     const uint32_t* tau_g;   // [nQT*kBN] ordered image of the phase threshold
     const unsigned char* zeros;   // 256 zero bytes (source of the chunks past the end of a row)
+    const int32_t* cond;     // not null: repeat of a warm search; cond[0] != 0 if any query tile needs it,
+                             // cond[1 + qt] != 0 if query tile qt does
 };
 
 // ---------------------------------------------------------------------------
@@ -231,6 +233,7 @@ template <typename T, bool KTAIL>
 __global__ __launch_bounds__(kMineThreads, 1)
 void mine_tile_kernel(const MineArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
+    if (a.cond != nullptr && a.cond[0] == 0) return;          // uniform: a repeat that is not needed
     // two stage buffers, each: W rows then Z rows
     constexpr int kStageBuf = (kBM + kBN) * kStageBytes;
     float* tau = reinterpret_cast<float*>(smem + 2 * kStageBuf);
@@ -284,6 +287,7 @@ void mine_tile_kernel(const MineArgs a) {
 
     for (; item < item_end; item += item_step) {
         const int64_t qtile = a.Qx > 0 ? item : item / a.S;
+        if (a.cond != nullptr && a.cond[1 + qtile] == 0) continue;     // uniform: this query tile came out complete
         const int slice = a.Qx > 0 ? slice_fixed : static_cast<int>(item % a.S);
         const int64_t t_begin = a.tile_lo + static_cast<int64_t>(slice) * a.tiles_per_slice;
         // tiles of the slice are counted from t_begin in 32 bits (a slice has at most 2^31 / 256 / 8 tiles)
@@ -605,10 +609,27 @@ void mine_tile_kernel(const MineArgs a) {
     }
 }
 
-__global__ void mine_init_kernel(uint32_t* tau_g, int32_t* gcnt, int64_t n, uint32_t* zeros /* [64] */) {
+__global__ void mine_init_kernel(uint32_t* tau_g, int32_t* gcnt, int64_t n, uint32_t* zeros /* [64] */,
+                                 const int32_t* cond) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i < n) { tau_g[i] = kTauInit; gcnt[i] = 0; }
     if (i < 64) zeros[i] = 0u;
+    if (i < n && (cond == nullptr || cond[1 + i / kBN] != 0)) { tau_g[i] = kTauInit; gcnt[i] = 0; }
+}
+
+// Start of a warm search: the thresholds the previous search left behind, lowered by rel * |tau|,
+// are the thresholds of one sweep over all labels.  Whatever they are, the outcome is exact: a query
+// that ends the sweep with fewer than k candidates raises the flag of its query tile, and the full
+// search is repeated for the flagged tiles.
+__global__ void mine_warm_init_kernel(uint32_t* tau_g, int32_t* gcnt, int64_t n, uint32_t* zeros /* [64] */,
+                                      int32_t* flag /* [1 + n / kBN] */, float rel) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const float t = ordered_to_float(tau_g[i]);
+        tau_g[i] = float_to_ordered(t - rel * fabsf(t));
+        gcnt[i] = 0;
+    }
+    if (i < 64) zeros[i] = 0u;
+    if (i <= n / kBN) flag[i] = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -689,16 +710,21 @@ constexpr int kSelectWaves = 4;
 __global__ __launch_bounds__(kSelectWaves * kWave)
 void mine_select_kernel(uint64_t* __restrict__ glist, int32_t* __restrict__ gcnt,
                         uint32_t* __restrict__ tau_g, int64_t Zq, int glist_cap, int k, int final_phase,
-                        int32_t* __restrict__ shortlist, float* __restrict__ scores) {
+                        int32_t* __restrict__ shortlist, float* __restrict__ scores,
+                        const int32_t* __restrict__ cond /* not null: only query tiles qt with cond[1 + qt] != 0 */,
+                        int32_t* __restrict__ short_flag /* not null: [0] and [1 + qt] are set when a query of tile qt
+                                                            has fewer than k candidates */) {
     __shared__ int hist[kSelectWaves][256];
     __shared__ uint64_t sorted[kSelectWaves][XC_MAX_K_MINE];
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
     const int64_t q = static_cast<int64_t>(blockIdx.x) * kSelectWaves + wave;
     if (q >= Zq) return;                               // wave-uniform; no workgroup barrier below
+    if (cond != nullptr && cond[1 + q / kBN] == 0) return;
     uint64_t* list = glist + static_cast<size_t>(q) * glist_cap;
     int n = gcnt[q];
     n = n < glist_cap ? n : glist_cap;
+    if (short_flag != nullptr && n < k && lane == 0) { short_flag[0] = 1; short_flag[1 + q / kBN] = 1; }
     if (n > k) {
         auto at = [list](int idx) { return list[idx]; };
         const float t = (n <= kSelectRegs / 2 * kWave) ? wave_select_k<kSelectRegs / 2>(list, at, n, k, hist[wave])
@@ -737,7 +763,7 @@ void mine_select_kernel(uint64_t* __restrict__ glist, int32_t* __restrict__ gcnt
 struct MinePlan {
     int64_t nQT, nLT;
     int kcap, nkb, glist_cap;
-    size_t off_lists, off_glist, off_gcnt, off_tau, off_zero, ws_bytes;
+    size_t off_flag, off_lists, off_glist, off_gcnt, off_tau, off_zero, ws_bytes;
     size_t lds_tile;
 };
 
@@ -782,6 +808,8 @@ static int plan_mine(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, MinePlan
     size_t off = 0;
     auto take = [&off](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
     const size_t nq = static_cast<size_t>(p->nQT) * kBN;
+    // first word: 1 if the last warm search had to repeat the full search for some query tile; then one word per tile
+    p->off_flag = take(4 * (static_cast<size_t>(p->nQT) + 1));
     p->off_lists = take(static_cast<size_t>(kMineGrid) * kBN * kCandCap * sizeof(uint64_t));
     p->off_glist = take(nq * p->glist_cap * sizeof(uint64_t));
     p->off_gcnt = take(nq * sizeof(int32_t));
@@ -804,14 +832,18 @@ extern "C" int xc_mine_workspace(int64_t Zq, int64_t L, int d, int k_h, xc_dtype
     return XC_OK;
 }
 
-extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64_t L, int d, int k_h,
-                                 xc_dtype t, int32_t* shortlist, float* scores, void* ws,
-                                 size_t ws_bytes, void* stream) {
-    using namespace xc;
+namespace xc {
+// The search proper.  warm: one sweep with the thresholds found in the workspace (lowered by
+// rel_margin * |tau|), then the full search if some query came out short; the kernels of the full
+// search are enqueued in any case and return at once when the flag says they are not needed.
+static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, int k_h, xc_dtype t,
+                    bool warm, float rel_margin, int32_t* shortlist, float* scores, void* ws,
+                    size_t ws_bytes, void* stream) {
     MinePlan p;
     const int rc = plan_mine(Zq, L, d, k_h, t, &p);
     if (rc != XC_OK) return rc;
     if (!Z || !W || !shortlist || !ws) return XC_EINVAL;
+    if (warm && !(rel_margin >= 0.0f)) return XC_EINVAL;
     if (!aligned16(Z) || !aligned16(W) || !aligned16(ws)) return XC_EINVAL;
     if (ws_bytes < p.ws_bytes) return XC_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -830,6 +862,8 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
     uint32_t* tau_g = reinterpret_cast<uint32_t*>(w8 + p.off_tau);
     a.tau_g = tau_g;
     a.zeros = w8 + p.off_zero;
+    a.cond = nullptr;
+    int32_t* flag = reinterpret_cast<int32_t*>(w8 + p.off_flag);
 
     // raise the dynamic LDS limit of the tile kernels: once per device and process (the attribute
     // belongs to the device's copy of the kernel)
@@ -851,15 +885,12 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
         }
     }
     const int64_t nq = p.nQT * kBN;
-    mine_init_kernel<<<dim3(static_cast<unsigned>((nq + 255) / 256)), 256, 0, st>>>(tau_g, a.gcnt, nq,
-                                                                                        reinterpret_cast<uint32_t*>(w8 + p.off_zero));
-    XC_HIP_CHECK(hipGetLastError());
+    const dim3 init_grid(static_cast<unsigned>((nq + 255) / 256));
+    const dim3 select_grid(static_cast<unsigned>((Zq + kSelectWaves - 1) / kSelectWaves));
+    uint32_t* zeros32 = reinterpret_cast<uint32_t*>(w8 + p.off_zero);
 
-    int64_t lo = 0;
-    while (lo < p.nLT) {
-        // phases end at about 1, 8, 64, ... tiles: each sees about 8x the labels seen before it
-        int64_t hi = lo + phase_tiles(lo, p.nQT);
-        if (hi > p.nLT || p.nLT - hi < hi / 4) hi = p.nLT;      // fold a short remainder into this phase
+    // one phase: the tile kernel over label tiles [lo, hi), then the select
+    auto phase = [&](int64_t lo, int64_t hi, const int32_t* cond, int32_t* short_flag) -> int {
         const int64_t nT = hi - lo;
         if (nT >= kXcds) {
             // slices per XCD: as many as the phase supports, so that few query tiles are in
@@ -876,6 +907,7 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
         a.tiles_per_slice = (nT + a.S - 1) / a.S;
         a.append_max = (p.glist_cap - p.kcap) / a.S;
         if (a.append_max > kCandCap) a.append_max = kCandCap;
+        a.cond = cond;
         const bool ktail = (a.row_bytes % kStageBytes) != 0;
         if (t == XC_BF16) {
             if (ktail) XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t, true><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));
@@ -886,11 +918,43 @@ extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64
         }
         XC_HIP_CHECK(hipGetLastError());
         const int final_phase = hi == p.nLT ? 1 : 0;
-        XC_LAUNCH(K_MINE_SELECT, st, (mine_select_kernel<<<dim3(static_cast<unsigned>((Zq + kSelectWaves - 1) / kSelectWaves)),
-                                                          kSelectWaves * kWave, 0, st>>>(
-            a.glist, a.gcnt, tau_g, Zq, p.glist_cap, k_h, final_phase, shortlist, scores)));
+        XC_LAUNCH(K_MINE_SELECT, st, (mine_select_kernel<<<select_grid, kSelectWaves * kWave, 0, st>>>(
+            a.glist, a.gcnt, tau_g, Zq, p.glist_cap, k_h, final_phase, shortlist, scores, cond, short_flag)));
         XC_HIP_CHECK(hipGetLastError());
+        return XC_OK;
+    };
+
+    const int32_t* cond = nullptr;
+    if (warm) {
+        mine_warm_init_kernel<<<init_grid, 256, 0, st>>>(tau_g, a.gcnt, nq, zeros32, flag, rel_margin);
+        XC_HIP_CHECK(hipGetLastError());
+        const int rcw = phase(0, p.nLT, nullptr, flag);
+        if (rcw != XC_OK) return rcw;
+        cond = flag;
+    }
+    mine_init_kernel<<<init_grid, 256, 0, st>>>(tau_g, a.gcnt, nq, zeros32, cond);
+    XC_HIP_CHECK(hipGetLastError());
+    int64_t lo = 0;
+    while (lo < p.nLT) {
+        // phases end at about 1, 8, 64, ... tiles: each sees about 8x the labels seen before it
+        int64_t hi = lo + phase_tiles(lo, p.nQT);
+        if (hi > p.nLT || p.nLT - hi < hi / 4) hi = p.nLT;      // fold a short remainder into this phase
+        const int rcp = phase(lo, hi, cond, nullptr);
+        if (rcp != XC_OK) return rcp;
         lo = hi;
     }
     return XC_OK;
+}
+}  // namespace xc
+
+extern "C" int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64_t L, int d, int k_h,
+                                 xc_dtype t, int32_t* shortlist, float* scores, void* ws,
+                                 size_t ws_bytes, void* stream) {
+    return xc::run_mine(Z, W, Zq, L, d, k_h, t, false, 0.0f, shortlist, scores, ws, ws_bytes, stream);
+}
+
+extern "C" int xc_mine_negatives_warm(const void* Z, const void* W, int64_t Zq, int64_t L, int d, int k_h,
+                                      xc_dtype t, float rel_margin, int32_t* shortlist, float* scores,
+                                      void* ws, size_t ws_bytes, void* stream) {
+    return xc::run_mine(Z, W, Zq, L, d, k_h, t, true, rel_margin, shortlist, scores, ws, ws_bytes, stream);
 }

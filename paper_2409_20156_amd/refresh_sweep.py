@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--taus", default="1,5,20,100")
+    ap.add_argument("--warm-margin", type=float, default=-1.0,
+                    help="refreshes after the first start from the previous thresholds lowered by this relative margin (negative: full search)")
     ap.add_argument("--lag", type=int, default=0, help="steps a refresh runs beside the training steps before it takes over (0 = synchronous)")
     args = ap.parse_args()
     dev = "cuda:0"
@@ -48,7 +50,8 @@ def main():
     for tau in [int(x) for x in args.taus.split(",")]:
         # timed run
         W, Z, pos = _job(wl, dev)
-        sch = Schedule(Z, W, pos, wl.B, wl.k_h, wl.k_r, 0, tau, wl.lr, lag=min(args.lag, tau))
+        sch = Schedule(Z, W, pos, wl.B, wl.k_h, wl.k_r, 0, tau, wl.lr, lag=min(args.lag, tau),
+                       warm_margin=args.warm_margin if args.warm_margin >= 0 else None)
         sch.step(seeds[0])                                   # first refresh and step: warm-up, untimed
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -56,9 +59,11 @@ def main():
             sch.step(seeds[t])
         torch.cuda.synchronize()
         el = time.perf_counter() - t0
+        full_repeats = int(sch.full_repeats.item())
         # overlap run (same trajectory: everything is deterministic)
         W, Z, pos = _job(wl, dev)
-        sch = Schedule(Z, W, pos, wl.B, wl.k_h, wl.k_r, 0, tau, wl.lr, lag=min(args.lag, tau))
+        sch = Schedule(Z, W, pos, wl.B, wl.k_h, wl.k_r, 0, tau, wl.lr, lag=min(args.lag, tau),
+                       warm_margin=args.warm_margin if args.warm_margin >= 0 else None)
         overlaps = []
         for t in range(args.steps):
             sch.step(seeds[t])
@@ -73,7 +78,9 @@ def main():
                           "refreshes_timed": sum(1 for t in range(1, args.steps) if t % tau == 0),
                           "steps_per_s": n / el, "queries_per_s": n * wl.B / el,
                           "mean_overlap_fresh_vs_stale": sum(overlaps) / len(overlaps) if overlaps else None,
-                          "min_overlap": min(overlaps) if overlaps else None}), flush=True)
+                          "min_overlap": min(overlaps) if overlaps else None,
+                          "warm_margin": args.warm_margin if args.warm_margin >= 0 else None,
+                          "warm_searches_repeated_in_full": full_repeats}), flush=True)
 
 
 if __name__ == "__main__":

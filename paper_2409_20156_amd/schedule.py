@@ -20,12 +20,16 @@ from . import binding as xc
 
 class Schedule:
     def __init__(self, Z_pool: torch.Tensor, W: torch.Tensor, pos_pool: torch.Tensor, B: int, k_h: int,
-                 k_r: int, tau_s: int, tau_r: int, lr: float, kind: int = xc.XC_LOSS_BCE, lag: int = 0):
+                 k_r: int, tau_s: int, tau_r: int, lr: float, kind: int = xc.XC_LOSS_BCE, lag: int = 0,
+                 warm_margin: float | None = None):
         if lag < 0 or (lag > 0 and lag > tau_r):
             raise ValueError("lag must lie in [0, tau_r]")
         self.Z, self.W, self.pos = Z_pool, W, pos_pool
         self.B, self.k_h, self.k_r, self.tau_s, self.tau_r, self.lr, self.kind = B, k_h, k_r, tau_s, tau_r, lr, kind
         self.lag = lag
+        self.warm_margin = warm_margin                 # refreshes after the first start from the last thresholds
+        self.searched = False
+        self.full_repeats = torch.zeros(1, dtype=torch.int32, device=W.device)   # warm searches that had to be repeated in full
         dev = W.device
         pool, d = Z_pool.shape
         L = W.shape[0]
@@ -75,7 +79,11 @@ class Schedule:
             nxt = 0 if self.built < 0 else 1 - self.built
             self.had_previous = self.built >= 0
             if self.lag == 0:
-                xc.mine_negatives(self.Z, self.W, self.k_h, workspace=self.mine_ws, out=self.shortlist[nxt])
+                warm = self.warm_margin if self.searched else None
+                xc.mine_negatives(self.Z, self.W, self.k_h, workspace=self.mine_ws, out=self.shortlist[nxt],
+                                  warm_margin=warm)
+                if warm is not None:
+                    self.full_repeats += self.mine_ws[:4].view(torch.int32)
                 self.cur = nxt
             else:
                 self.W_snap.copy_(self.W)                                      # on the step stream
@@ -84,10 +92,15 @@ class Schedule:
                 done = torch.cuda.Event()
                 with torch.cuda.stream(self.side):
                     self.side.wait_event(snap_done)
-                    xc.mine_negatives(self.Z, self.W_snap, self.k_h, workspace=self.mine_ws, out=self.shortlist[nxt])
+                    warm = self.warm_margin if self.searched else None
+                    xc.mine_negatives(self.Z, self.W_snap, self.k_h, workspace=self.mine_ws, out=self.shortlist[nxt],
+                                      warm_margin=warm)
+                    if warm is not None:
+                        self.full_repeats += self.mine_ws[:4].view(torch.int32)
                     done.record(self.side)
                 self.pending = (t + self.lag, nxt, done)
             self.built = nxt
+            self.searched = True
             self.refreshed = True
         b = t % self.nbatch
         lo, hi = b * self.B, (b + 1) * self.B

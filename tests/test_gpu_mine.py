@@ -114,3 +114,62 @@ def test_inference_topk_precision_on_planted_positives():
     p5 = float((ids == truth[:, None]).any(axis=1).mean())
     assert p1 == float((ids_o[:, 0] == truth).mean()) and p5 == float((ids_o == truth[:, None]).any(axis=1).mean())
     assert p1 > 0.9 and p5 >= p1
+
+
+def _fallback_flag(ws):
+    torch.cuda.synchronize()
+    return int(ws[:4].view(torch.int32).item())
+
+
+def test_warm_search_is_exact_whatever_the_workspace_holds():
+    """The warm search starts from the thresholds left in the workspace; the result must equal the
+    oracle's in every case: thresholds that still fit (one sweep), thresholds that a changed W
+    has overtaken (the call repeats the full search), and a workspace that never saw a search."""
+    import paper_2409_20156_amd as xc
+    dev = "cuda:0"
+    Zq, L, d, k = 300, 20000, 64, 50
+    Z = synth.make_matrix(3, synth.TAG_Z, Zq, d, torch.bfloat16, dev)
+    W = synth.make_matrix(3, synth.TAG_W, L, d, torch.bfloat16, dev)
+    Z64 = f64(Z)
+    ws = torch.empty(xc.mine_workspace(Zq, L, d, k, xc.XC_BF16), dtype=torch.uint8, device=dev)
+
+    def check(Wc, ids, sc):
+        ids_o, sc_o = orc.mine_negatives(Z64, f64(Wc), k)
+        check_topk(ids.cpu().numpy(), sc.cpu().numpy(), ids_o, sc_o, Z64, f64(Wc))
+
+    # a workspace with arbitrary content: nothing to start from
+    ws.random_(0, 255)
+    ids, sc = xc.mine_negatives(Z, W, k, want_scores=True, workspace=ws, warm_margin=0.1)
+    check(W, ids, sc)
+    # same W again: the old k-th scores are exact thresholds, even with no margin
+    ids, sc = xc.mine_negatives(Z, W, k, want_scores=True, workspace=ws, warm_margin=0.0)
+    assert _fallback_flag(ws) == 0
+    check(W, ids, sc)
+    # a small drift of every row: the margin covers it
+    W2 = (W.float() + 0.002 * synth.make_matrix(4, synth.TAG_W, L, d, torch.float32, dev)).to(torch.bfloat16)
+    ids, sc = xc.mine_negatives(Z, W2, k, want_scores=True, workspace=ws, warm_margin=0.2)
+    assert _fallback_flag(ws) == 0
+    check(W2, ids, sc)
+    # W shrunk to a tenth: every score falls far below its old threshold -> full search
+    W3 = (W2.float() * 0.1).to(torch.bfloat16)
+    ids, sc = xc.mine_negatives(Z, W3, k, want_scores=True, workspace=ws, warm_margin=0.05)
+    assert _fallback_flag(ws) == 1
+    check(W3, ids, sc)
+    # only some queries overtaken (their embeddings shrunk): the full search is repeated for their
+    # tile of 256 queries, the other tile keeps the result of the sweep
+    ids, sc = xc.mine_negatives(Z, W3, k, want_scores=True, workspace=ws)
+    Zp = Z.clone()
+    Zp[10:60] = (Zp[10:60].float() * 0.05).to(torch.bfloat16)
+    ids, sc = xc.mine_negatives(Zp, W3, k, want_scores=True, workspace=ws, warm_margin=0.05)
+    assert _fallback_flag(ws) == 1
+    flags = ws[:12].view(torch.int32).cpu().numpy()
+    assert flags[1] == 1 and flags[2] == 0
+    ids_o, sc_o = orc.mine_negatives(f64(Zp), f64(W3), k)
+    check_topk(ids.cpu().numpy(), sc.cpu().numpy(), ids_o, sc_o, f64(Zp), f64(W3))
+    # a margin so wide that nearly every score passes: slow, still exact
+    ids, sc = xc.mine_negatives(Z, W3, k, want_scores=True, workspace=ws, warm_margin=50.0)
+    assert _fallback_flag(ws) == 0
+    check(W3, ids, sc)
+    # the cold call is unaffected by what the warm ones left
+    ids, sc = xc.mine_negatives(Z, W, k, want_scores=True, workspace=ws)
+    check(W, ids, sc)

@@ -14,8 +14,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("kind,lag", [(orc.LOSS_BCE, 0), (orc.LOSS_SOFTMAX, 0), (orc.LOSS_BCE, 2), (orc.LOSS_BCE, 1)])
-def test_schedule_matches_oracle(kind, lag):
+@pytest.mark.parametrize("kind,lag,warm", [(orc.LOSS_BCE, 0, None), (orc.LOSS_SOFTMAX, 0, None), (orc.LOSS_BCE, 2, None),
+                                           (orc.LOSS_BCE, 1, None), (orc.LOSS_BCE, 0, 0.1), (orc.LOSS_BCE, 2, 0.0)])
+def test_schedule_matches_oracle(kind, lag, warm):
     from paper_2409_20156_amd.schedule import Schedule
     L, d, B, pool, k_p, k_h, k_r = 4096, 64, 32, 64, 2, 8, 16
     steps, tau_s, tau_r, lr = 7, 1, 2, 0.3
@@ -28,7 +29,9 @@ def test_schedule_matches_oracle(kind, lag):
     ref = orc.train_schedule(Z64, W64, pos, B, k_h, k_r, steps, tau_s, tau_r, lr, seeds, kind=kind, storage="f32",
                              lag=lag)
 
-    sch = Schedule(Z, W, torch.tensor(pos, device=DEV), B, k_h, k_r, tau_s, tau_r, lr, kind=kind, lag=lag)
+    # warm: refreshes after the first start from the last thresholds (same shortlists, by either route)
+    sch = Schedule(Z, W, torch.tensor(pos, device=DEV), B, k_h, k_r, tau_s, tau_r, lr, kind=kind, lag=lag,
+                   warm_margin=warm)
     tol = 20 * TOL["f32"]                  # rounding differences compound over the steps
     n_ref, overlaps = 0, []
     for t in range(steps):
