@@ -66,6 +66,8 @@ def test_host_side_argument_checks(lib):
     assert b.xc_mfma_probe(None, 10, 1, None, None) == -1
     assert b.xc_copy_probe(None, None, 64, None) == -1
     assert b.xc_mine_negatives(None, None, 1, 100, 64, 8, 1, None, None, None, 0, None) == -1
+    assert b.xc_mine_negatives_warm(None, None, 1, 100, 64, 8, 1, 0.1, None, None, None, 0, None) == -1
+    assert b.xc_mine_negatives_warm(None, None, 1, 100, 64, 200, 1, 0.1, None, None, None, 0, None) == -2   # k_h > L
     assert b.xc_step(None, None, 32, 4096, 64, None, 1, None, None, 24, 0.1, 0, 0, None, None, None,
                      None, None, None, big, None) == -1
     assert b.xc_strerror(-2).decode().startswith("unsupported")

@@ -28,6 +28,12 @@ def test_workspace_too_small_and_misaligned_pointers_are_rejected():
     rc = lib.xc_mine_negatives(Z.data_ptr() + 2, W.data_ptr(), Zq, L, d, k, xc.XC_BF16, out.data_ptr(), None,
                                ws.data_ptr(), need, st)
     assert rc == -1                                              # misaligned Z
+    rc = lib.xc_mine_negatives_warm(Z.data_ptr(), W.data_ptr(), Zq, L, d, k, xc.XC_BF16, ctypes.c_float(-0.5),
+                                    out.data_ptr(), None, ws.data_ptr(), need, st)
+    assert rc == -1                                              # a negative margin
+    rc = lib.xc_mine_negatives_warm(Z.data_ptr(), W.data_ptr(), Zq, L, d, k, xc.XC_BF16, ctypes.c_float(float("nan")),
+                                    out.data_ptr(), None, ws.data_ptr(), need, st)
+    assert rc == -1
     torch.cuda.synchronize()
     assert (out == -7).all() and not ws.any()                    # nothing ran
     assert lib.xc_strerror(-3).decode().startswith("workspace")
