@@ -130,7 +130,9 @@ __device__ __forceinline__ int lane_of_row(int u, int G) {      // lowest lane o
 // (G = 16, 32 or 64) owns one candidate row at a time, lane gl of the group
 // holding the 16-byte chunks gl, gl+G, ... of the row (CPL chunks per lane).
 // ---------------------------------------------------------------------------
-template <typename T, int CPL, int KIND, int U>
+// FULL: every lane's CPL chunks exist (d / kPerChunk == G * CPL), so no load needs a bounds test; a masked
+// pair then reads the query's own row (finite, and weighted zero) instead of branching around the loads.
+template <typename T, int CPL, int KIND, int U, bool FULL>
 __global__ __launch_bounds__(kStepThreads)
 void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, int d,
                    const int32_t* __restrict__ pos, int k_p, const int32_t* __restrict__ neg,
@@ -227,12 +229,20 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
                 for (int q = G + gl; q < k_p; q += G) hit = hit || spos[q] == id[u];
                 ok[u] = ok[u] && (__ballot(hit) & grp_mask) == 0ull;
             }
+            if (FULL) {
+                const unsigned char* src = ok[u] ? Wb + static_cast<int64_t>(id[u]) * row_bytes
+                                                 : reinterpret_cast<const unsigned char*>(Z) + i * row_bytes;
 #pragma unroll
-            for (int j = 0; j < CPL; ++j) {
-                const int ch = gl + j * G;
-                rw[u][j] = make_uint4(0, 0, 0, 0);
-                if (ok[u] && ch < nchunks)
-                    rw[u][j] = *reinterpret_cast<const uint4*>(Wb + static_cast<int64_t>(id[u]) * row_bytes + ch * 16);
+                for (int j = 0; j < CPL; ++j)
+                    rw[u][j] = *reinterpret_cast<const uint4*>(src + (gl + j * G) * 16);
+            } else {
+#pragma unroll
+                for (int j = 0; j < CPL; ++j) {
+                    const int ch = gl + j * G;
+                    rw[u][j] = make_uint4(0, 0, 0, 0);
+                    if (ok[u] && ch < nchunks)
+                        rw[u][j] = *reinterpret_cast<const uint4*>(Wb + static_cast<int64_t>(id[u]) * row_bytes + ch * 16);
+                }
             }
         }
         fetch_ids(c0 + NG * U);
@@ -291,8 +301,8 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u * NG;
             const int src = grp_lane0 + lane_of_row<U>(u, G);
-            const float g = __shfl(my_g, src, kWave);
-            if (ok[u]) {
+            const float g = __shfl(my_g, src, kWave);    // zero for a masked pair
+            if (FULL || ok[u]) {
                 float wf[CPL][EPC];
 #pragma unroll
                 for (int j = 0; j < CPL; ++j) {
@@ -300,7 +310,7 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
 #pragma unroll
                     for (int e = 0; e < EPC; ++e) dz[j][e] = fmaf(g, wf[j][e], dz[j][e]);
                 }
-                if (KIND == XC_LOSS_SOFTMAX && isp[u]) {
+                if (KIND == XC_LOSS_SOFTMAX && isp[u] && ok[u]) {
 #pragma unroll
                     for (int j = 0; j < CPL; ++j)
 #pragma unroll
@@ -1106,16 +1116,17 @@ static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, con
                           float* loss_q, float* dZ, int SQ) {
     const float inv_B = 1.0f / static_cast<float>(B);
     const dim3 grid(static_cast<unsigned>(B * SQ));
+#define XC_GATHER2(CPL, UU, FF)                                                                        \
+    XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, UU, FF><<<grid, kStepThreads, 0, st>>>(         \
+        static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg,          \
+        pl.G, SQ, B, inv_B, keys, vals, gco, loss_q, dZ)))
 #define XC_GATHER(CPL)                                                                                 \
     do {                                                                                               \
+        const bool full = (d / Elem<T>::kPerChunk) == pl.G * CPL && d % Elem<T>::kPerChunk == 0;       \
         if (B * SQ <= 1024) {   /* few workgroups: more rows in flight per group */                   \
-            XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, 8><<<grid, kStepThreads, 0, st>>>(    \
-                static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg,  \
-                pl.G, SQ, B, inv_B, keys, vals, gco, loss_q, dZ)));                                    \
+            if (full) XC_GATHER2(CPL, 8, true); else XC_GATHER2(CPL, 8, false);                        \
         } else {                                                                                       \
-            XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, 4><<<grid, kStepThreads, 0, st>>>(    \
-                static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg,  \
-                pl.G, SQ, B, inv_B, keys, vals, gco, loss_q, dZ)));                                    \
+            if (full) XC_GATHER2(CPL, 4, true); else XC_GATHER2(CPL, 4, false);                        \
         }                                                                                              \
     } while (0)
     switch (pl.cpl) {
@@ -1125,6 +1136,7 @@ static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, con
         default: XC_GATHER(4); break;
     }
 #undef XC_GATHER
+#undef XC_GATHER2
 }
 
 template <typename T>
