@@ -169,6 +169,17 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     value = wl.B * args.steps / elapsed
+    # for comparison, the same number of steps with a full search at every refresh (untimed for `value`)
+    full_search = None
+    if job.warm_margin is not None and wl.refresh and not args.no_profile_pass:
+        job.warm_margin = None
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            job.step()
+        torch.cuda.synchronize()
+        el1 = time.perf_counter() - t1
+        full_search = {"value": wl.B * args.steps / el1, "ms_per_step": el1 * 1e3 / args.steps}
+        job.warm_margin = args.warm_margin
 
     if args.copy_probe_mib:
         a = torch.randint(0, 255, (args.copy_probe_mib << 20,), dtype=torch.uint8, device="cuda:0")
@@ -251,6 +262,7 @@ def main():
                    "refresh_search": ("exact, warm start from the previous thresholds (margin %g)" % args.warm_margin)
                                      if args.warm_margin >= 0 else "exact, full search every time"},
         "roofline": roofline,
+        "full_search_every_refresh": full_search,
         "kernels_us": {n: round(k["avg_us"], 2) for n, k in kernels.items()},
     }
     # ---- what the chip sustains on two trivial kernels (context for the fractions above) -----
