@@ -457,6 +457,11 @@ void mine_tile_kernel(const MineArgs a) {
 
 
             // ---- threshold filter: lane owns query column (lane & 31) of each N tile
+            const bool last = tile + 1 == n_tiles;
+            // The flag this tile may set shares its slot with the flag of two tiles back, which the waves
+            // read after the previous tile's filter: a barrier has to lie between that read and this
+            // tile's filter.  Every tile has one in its main loop except a one-stage last tile.
+            if (last && a.nkb == 1) __syncthreads();
             bool grew = false;                               // this wave emptied its pool during the tile
             auto filter = [&](auto ntc) {
                 constexpr int nt = decltype(ntc)::value;
@@ -528,8 +533,6 @@ void mine_tile_kernel(const MineArgs a) {
             // A list that could overflow before the next look (two tiles add at most 2 kBM entries, the
             // two pools that feed it at most kPoolKeep each), or, at the end of the slice, exceeds what
             // a slice may append, is cut to its best k and tau rises for the rest of the slice.
-            const bool last = tile + 1 == n_tiles;
-            if (last) __syncthreads();                       // (a one-stage tile has no barrier of its own)
             if (last || dirty[par ^ 1] != 0) {               // uniform
                 __syncthreads();                             // the pools' stores to the lists are complete
                 const int qloc = wave * 32 + (lane & 31);

@@ -39,6 +39,13 @@ def _case(seed, Zq, L, d, dtype, k):
     (3, 64, 64, torch.bfloat16, 64),           # k = L, single partial tile
     (257, 3000, 768, torch.bfloat16, 128),     # maximum k, d of the large configurations
     (5, 129, 8, torch.bfloat16, 7),            # minimum row (16 bytes)
+    # 128-byte rows are one pipeline stage per tile, and query tiles with few real queries leave half
+    # of the waves with nothing to filter: they run a tile ahead of the others
+    (78, 30000, 64, torch.bfloat16, 63),
+    (200, 30000, 64, torch.bfloat16, 63),
+    (600, 30000, 64, torch.bfloat16, 63),
+    (78, 30000, 32, torch.float32, 63),
+    (78, 16384, 64, torch.bfloat16, 8),
 ])
 def test_mine_matches_oracle(Zq, L, d, dtype, k):
     print("case", Zq, L, d, dtype, k, flush=True)
