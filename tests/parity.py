@@ -64,19 +64,24 @@ def check_bf16_rows(got, want, old, what, max_mismatch_frac=2e-3, slack=None):
     the operands (2^-18 of the larger of old and new element: sums in float32 and
     hardware exp2/log2/rcp in the coefficients) is allowed on top.  `slack`
     (per row, optional) adds the float32 error of a gradient sum whose terms cancel:
-    the caller passes about 2e-6 * lr * sum|g| * max|z| of the row."""
+    the caller passes about 2e-6 * lr * sum|g| * max|z| of the row.
+    One ulp is up to 2^-7 of the element, so in a row of fewer than 64 elements a
+    single such straddle can by itself exceed 2e-3 of the row's norm: there the
+    norm-wise bar is applied to the differences beyond one ulp, and the straddles
+    are bounded by the element-wise test and their count alone."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     old = np.asarray(old, dtype=np.float64)
     assert got.shape == want.shape == old.shape
     if got.size == 0:
         return
-    num = np.linalg.norm(got - want, axis=-1)
-    den = np.maximum(np.linalg.norm(want, axis=-1), 1e-30)
-    assert (num / den).max() <= 2e-3, (what, (num / den).max())
     _, e = np.frexp(np.maximum(np.abs(want), np.abs(got)))
     ulp = np.ldexp(1.0, np.maximum(e, -125) - 8)
     diff = np.abs(got - want)
+    counted = diff if got.shape[-1] >= 64 else np.where(diff <= ulp * 1.0000001, 0.0, diff)
+    num = np.linalg.norm(counted, axis=-1)
+    den = np.maximum(np.linalg.norm(want, axis=-1), 1e-30)
+    assert (num / den).max() <= 2e-3, (what, (num / den).max())
     allowed = ulp * 1.0000001 + 2.0 ** -18 * np.maximum(np.abs(old), np.abs(want))
     if slack is not None:
         allowed = allowed + np.asarray(slack, dtype=np.float64).reshape(-1, 1)
