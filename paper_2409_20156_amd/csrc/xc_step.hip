@@ -499,7 +499,8 @@ __global__ __launch_bounds__(kSortTile)
 void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
                           uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, int64_t P,
                           int64_t chunk, int shift, int rb, int nb, const int* __restrict__ prefix,
-                          const int* __restrict__ totals, uint32_t inv_key, int inv_digit) {
+                          const int* __restrict__ totals, uint32_t inv_key, int inv_digit,
+                          int* __restrict__ bases_out /* [radix] or null: where each digit's pairs start */) {
     extern __shared__ int sort_lds[];                  // offs[radix], whist[waves][radix]: sized by the launch
     __shared__ int wsum[kSortTile / kWave];
     const int tid = threadIdx.x;
@@ -519,7 +520,11 @@ void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* 
         for (int w = 0; w < wave; ++w) run += wsum[w];
         for (int j = 0; j < per; ++j) {
             const int d = tid * per + j;
-            if (d < radix) { offs[d] = run + prefix[d * nb + blockIdx.x]; run += totals[d]; }
+            if (d < radix) {
+                if (bases_out != nullptr && blockIdx.x == 0) bases_out[d] = run;
+                offs[d] = run + prefix[d * nb + blockIdx.x];
+                run += totals[d];
+            }
         }
     }
     for (int d = tid; d < radix; d += kSortTile)
@@ -554,7 +559,8 @@ constexpr int64_t kBucketTarget = XC_BUCKET_TARGET;   // pairs per bucket the di
 __global__ __launch_bounds__(kSortTile)
 void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
                         uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out,
-                        const int* __restrict__ sizes /* [gridDim.x] pairs per bucket */, int rb,
+                        const int* __restrict__ sizes /* [gridDim.x] pairs per bucket */,
+                        const int* __restrict__ bases /* [gridDim.x] first pair of each bucket */, int rb,
                         int* __restrict__ head_cnt /* [gridDim.x] */) {
     extern __shared__ int sort_lds[];                  // offs[radix], whist[waves][radix]: sized by the launch
     __shared__ int wsum[kSortTile / kWave];
@@ -565,24 +571,14 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
     int* offs = sort_lds;
     int* whist = sort_lds + radix;
     const int b = blockIdx.x;
-    {   // where the bucket starts: the sizes of the buckets before it
-        int t = 0;
-        for (int j = tid; j < b; j += kSortTile) t += sizes[j];
-        red[tid] = t;
-    }
+    const int p0 = bases[b];
+    const int p1 = p0 + sizes[b];
     for (int d = tid; d < radix; d += kSortTile) {
         offs[d] = 0;
 #pragma unroll
         for (int w = 0; w < kSortTile / kWave; ++w) whist[w * radix + d] = 0;
     }
     __syncthreads();
-    for (int s2 = kSortTile / 2; s2 > 0; s2 >>= 1) {
-        if (tid < s2) red[tid] += red[tid + s2];
-        __syncthreads();
-    }
-    const int p0 = red[0];
-    const int p1 = p0 + sizes[b];
-    __syncthreads();                                   // red is reused below
     const bool in_regs = p1 - p0 <= kBucketRegTiles * kSortTile;        // uniform
     uint32_t rk[kBucketRegTiles], rv[kBucketRegTiles];
     if (in_regs) {
@@ -683,24 +679,14 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
                         int32_t* __restrict__ seg_start, uint32_t* __restrict__ seg_idx0,
                         int32_t* __restrict__ n_touched, const float* __restrict__ loss_q, int64_t B,
                         float inv_B, float* __restrict__ loss, int SQ,
-                        const int* __restrict__ bucket_sizes /* not null: block b covers bucket b */) {
+                        const int* __restrict__ bucket_sizes /* not null: block b covers bucket b ... */,
+                        const int* __restrict__ bucket_bases /* ... which starts at pair bucket_bases[b] */) {
     __shared__ int sh[256];
     __shared__ int wcnt[4];
     __shared__ int running;
-    __shared__ int bucket_p0;
     const int tid = threadIdx.x;
-    if (bucket_sizes) {                 // first position of this block's bucket
-        int t0 = 0;
-        for (int b = tid; b < static_cast<int>(blockIdx.x); b += 256) t0 += bucket_sizes[b];
-        sh[tid] = t0;
-        __syncthreads();
-        for (int s = 128; s > 0; s >>= 1) {
-            if (tid < s) sh[tid] += sh[tid + s];
-            __syncthreads();
-        }
-        if (tid == 0) bucket_p0 = sh[0];
-        __syncthreads();
-    }
+    int bucket_p0 = 0, bucket_n = 0;
+    if (bucket_sizes) { bucket_p0 = bucket_bases[blockIdx.x]; bucket_n = bucket_sizes[blockIdx.x]; }
     // heads in the blocks before this one
     int t = 0;
     for (int b = tid; b < static_cast<int>(blockIdx.x); b += 256) t += head_cnt[b];
@@ -737,7 +723,7 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
     }
     int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
-    if (bucket_sizes) { p0 = bucket_p0; p1 = p0 + bucket_sizes[blockIdx.x]; }
+    if (bucket_sizes) { p0 = bucket_p0; p1 = p0 + bucket_n; }
     p1 = p1 < P ? p1 : P;
     for (int64_t t0 = p0; t0 < p1; t0 += 256) {
         const int64_t p = t0 + tid;
@@ -1026,7 +1012,7 @@ struct StepPlan {
     int low_bits, n_buckets, high_rb;       // n_buckets > 0: one round on the high digit, then bucket_sort
     uint32_t n_magic;
     int64_t chunk;
-    size_t off_keys0, off_keys1, off_vals0, off_vals1, off_g, off_lossq, off_dzpart, off_counts, off_totals, off_headcnt,
+    size_t off_keys0, off_keys1, off_vals0, off_vals1, off_g, off_lossq, off_dzpart, off_counts, off_totals, off_bases, off_headcnt,
         off_validcnt, off_segstart, off_segidx0, total;
 };
 
@@ -1101,6 +1087,7 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     p->off_dzpart = take(p->sq > 1 ? static_cast<size_t>(B) * p->sq * d * 4 : 0);
     p->off_counts = take(static_cast<size_t>(kSortCountEntries) * 4);      // whatever L: the layout does not depend on it
     p->off_totals = take(static_cast<size_t>(kMaxRadix) * 4);
+    p->off_bases = take(static_cast<size_t>(kMaxRadix) * 4);
     p->off_headcnt = take(static_cast<size_t>(kSortMaxBlocks > kMaxRadix ? kSortMaxBlocks : kMaxRadix) * 4);
     p->off_validcnt = take(static_cast<size_t>(kSortMaxBlocks) * 4);
     p->off_segstart = take((P + 1) * 4);
@@ -1206,6 +1193,7 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
     float* loss_q = reinterpret_cast<float*>(w8 + pl.off_lossq);
     int* counts = reinterpret_cast<int*>(w8 + pl.off_counts);
     int* totals = reinterpret_cast<int*>(w8 + pl.off_totals);
+    int* bases = reinterpret_cast<int*>(w8 + pl.off_bases);
     int* head_cnt = reinterpret_cast<int*>(w8 + pl.off_headcnt);
     int* valid_cnt = reinterpret_cast<int*>(w8 + pl.off_validcnt);
     int32_t* seg_start = reinterpret_cast<int32_t*>(w8 + pl.off_segstart);
@@ -1235,12 +1223,12 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
         const uint32_t Lk = static_cast<uint32_t>(L);
         XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, Lk, pl.n_buckets)));
         XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
-        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.high_rb), st>>>(kin, vin, kout, vout, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, totals, Lk, pl.n_buckets)));
-        XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, sort_lds_bytes(pl.low_bits), st>>>(kout, vout, kin, vin, totals, pl.low_bits, head_cnt)));
+        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.high_rb), st>>>(kin, vin, kout, vout, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, totals, Lk, pl.n_buckets, bases)));
+        XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, sort_lds_bytes(pl.low_bits), st>>>(kout, vout, kin, vin, totals, bases, pl.low_bits, head_cnt)));
         // the sizes of the label buckets add up to the number of unmasked pairs
         XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.n_buckets, 256, 0, st>>>(kin, pl.P, pl.chunk, Lk, pl.n_buckets, head_cnt,
                                                                                      totals, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
-                                                                                     1.0f / static_cast<float>(B), loss, SQ, totals)));
+                                                                                     1.0f / static_cast<float>(B), loss, SQ, totals, bases)));
         XC_HIP_CHECK(hipGetLastError());
     } else {
         for (int pass = 0; pass < pl.passes; ++pass) {
@@ -1248,7 +1236,7 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
             const int radix = 1 << pl.rb;
             XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, 0xffffffffu, 0)));
             XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
-            XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.rb), st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals, 0xffffffffu, 0)));
+            XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.rb), st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals, 0xffffffffu, 0, nullptr)));
             XC_HIP_CHECK(hipGetLastError());
             uint32_t* tk = kin; kin = kout; kout = tk;
             uint32_t* tv = vin; vin = vout; vout = tv;
@@ -1256,7 +1244,7 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
         XC_LAUNCH(K_HEADS_COUNT, st, (heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt)));
         XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
                                                                                 valid_cnt, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
-                                                                                1.0f / static_cast<float>(B), loss, SQ, nullptr)));
+                                                                                1.0f / static_cast<float>(B), loss, SQ, nullptr, nullptr)));
         XC_HIP_CHECK(hipGetLastError());
     }
     if (t == XC_BF16) launch_update<bf16_t>(pl, st, Z, W, d, vin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
