@@ -43,14 +43,17 @@ def check_topk(ids_gpu, sc_gpu, ids_or, sc_or, Z64, W64, tie_rel=1e-5, score_rto
     return n_tied
 
 
-def check_rows_close(got, want, tol, what):
-    """Per row: max abs error relative to the row's largest magnitude."""
+def check_rows_close(got, want, tol, what, floor=None):
+    """Per row: max abs error relative to the row's largest magnitude, or to `floor`
+    (per row) where that is larger: the size of the terms of a sum that cancels."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, (what, got.shape, want.shape)
     if got.size == 0:
         return 0.0
     scale = np.maximum(np.abs(want).max(axis=-1, keepdims=True), 1e-30)
+    if floor is not None:
+        scale = np.maximum(scale, np.asarray(floor, dtype=np.float64).reshape(-1, 1))
     err = (np.abs(got - want) / scale).max()
     assert err <= tol, "%s: relative error %.3e > %.1e" % (what, err, tol)
     return err
