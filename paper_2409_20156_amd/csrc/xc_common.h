@@ -114,6 +114,27 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
+// 16-byte global accesses with the non-temporal hint: the line is marked for early replacement, so data
+// that is touched once (rows of a matrix much larger than the caches) does not push out what is reused.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+template <bool STREAM>
+__device__ __forceinline__ uint4 load16(const void* p) {
+    if (STREAM) {
+        const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+        return make_uint4(v.x, v.y, v.z, v.w);
+    }
+    return *reinterpret_cast<const uint4*>(p);
+}
+template <bool STREAM>
+__device__ __forceinline__ void store16(void* p, uint4 o) {
+    if (STREAM) {
+        u32x4_t v;
+        v.x = o.x; v.y = o.y; v.z = o.z; v.w = o.w;
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(p));
+    } else {
+        *reinterpret_cast<uint4*>(p) = o;
+    }
+}
 __device__ __forceinline__ uint64_t lanemask_lt() {
     return (1ull << lane_id()) - 1ull;
 }

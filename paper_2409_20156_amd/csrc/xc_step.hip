@@ -132,7 +132,7 @@ __device__ __forceinline__ int lane_of_row(int u, int G) {      // lowest lane o
 // ---------------------------------------------------------------------------
 // FULL: every lane's CPL chunks exist (d / kPerChunk == G * CPL), so no load needs a bounds test; a masked
 // pair then reads the query's own row (finite, and weighted zero) instead of branching around the loads.
-template <typename T, int CPL, int KIND, int U, bool FULL>
+template <typename T, int CPL, int KIND, int U, bool FULL, bool STREAM>
 __global__ __launch_bounds__(kStepThreads)
 void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, int d,
                    const int32_t* __restrict__ pos, int k_p, const int32_t* __restrict__ neg,
@@ -234,7 +234,7 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
                                                  : reinterpret_cast<const unsigned char*>(Z) + i * row_bytes;
 #pragma unroll
                 for (int j = 0; j < CPL; ++j)
-                    rw[u][j] = *reinterpret_cast<const uint4*>(src + (gl + j * G) * 16);
+                    rw[u][j] = load16<STREAM>(src + (gl + j * G) * 16);
             } else {
 #pragma unroll
                 for (int j = 0; j < CPL; ++j) {
@@ -755,7 +755,7 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
 constexpr int kLongSeg = 16;        // pairs above which a segment is shared by the workgroup
 constexpr int kMaxLong = 32;        // queued long segments per workgroup (more are done in place)
 
-template <typename T, int CPL>
+template <typename T, int CPL, bool STREAM>
 __global__ __launch_bounds__(kStepThreads)
 void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n_magic, int n_shift, int G,
                    const uint32_t* __restrict__ vals, const float* __restrict__ gco,
@@ -811,7 +811,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
             wv[j] = make_uint4(0, 0, 0, 0);
             z0[j] = make_uint4(0, 0, 0, 0);
             if (ch < nchunks) {
-                wv[j] = *reinterpret_cast<const uint4*>(wr + ch * 16);
+                wv[j] = load16<STREAM>(wr + ch * 16);
                 z0[j] = *reinterpret_cast<const uint4*>(Zb + qi * row_bytes + ch * 16);
             }
         }
@@ -907,8 +907,8 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
 #pragma unroll
             for (int e = 0; e < EPC; ++e) wf[e] = fmaf(-lr, acc[j][e], wf[e]);
             const uint4 o = Elem<T>::pack(wf);
-            *reinterpret_cast<uint4*>(wrow + ch * 16) = o;
-            if (orow) *reinterpret_cast<uint4*>(orow + ch * 16) = o;
+            store16<STREAM>(wrow + ch * 16, o);
+            if (orow) store16<STREAM>(orow + ch * 16, o);
         }
     }
     }   // segments of this group
@@ -979,7 +979,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
             for (int j = 0; j < CPL; ++j) {
                 const int ch = gl + j * G;
                 if (ch < nchunks) {
-                    const uint4 wv = *reinterpret_cast<const uint4*>(wrow + ch * 16);
+                    const uint4 wv = load16<STREAM>(wrow + ch * 16);
                     float tot[EPC];
 #pragma unroll
                     for (int e = 0; e < EPC; ++e) tot[e] = lpart[((0 * CPL + j) * G + gl) * EPC + e];
@@ -991,8 +991,8 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
 #pragma unroll
                     for (int e = 0; e < EPC; ++e) wf[e] = fmaf(-lr, tot[e], wf[e]);
                     const uint4 o = Elem<T>::pack(wf);
-                    *reinterpret_cast<uint4*>(wrow + ch * 16) = o;
-                    if (orow) *reinterpret_cast<uint4*>(orow + ch * 16) = o;
+                    store16<STREAM>(wrow + ch * 16, o);
+                    if (orow) store16<STREAM>(orow + ch * 16, o);
                 }
             }
         }
@@ -1010,6 +1010,7 @@ struct StepPlan {
     int64_t P;
     int n, G, cpl, nb, passes, rb, key_bits, sq, n_shift;
     int low_bits, n_buckets, high_rb;       // n_buckets > 0: one round on the high digit, then bucket_sort
+    bool stream_update, stream_gather;      // rows of W go through the caches with the non-temporal hint
     uint32_t n_magic;
     int64_t chunk;
     size_t off_keys0, off_keys1, off_vals0, off_vals1, off_g, off_lossq, off_dzpart, off_counts, off_totals, off_bases, off_headcnt,
@@ -1025,6 +1026,15 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     if (row_bytes % 16 != 0 || row_bytes > XC_MAX_ROW_BYTES) return XC_ESHAPE;
     if (B * n >= 0x7fffffffLL) return XC_ESHAPE;
     p->P = B * n;
+    // A matrix that fits the 256 MB last-level cache is found there again by the update after the gather and
+    // by the next step, so its rows are loaded and stored plainly.  A larger one is streamed by the update
+    // (every touched row is read and written once, and the query rows it reads many times stay cached), and,
+    // from about six times that size, where a gathered row is unlikely to be found again, by the gather too.
+    {
+        const int64_t w_bytes = L * row_bytes;
+        p->stream_update = w_bytes > (static_cast<int64_t>(256) << 20);
+        p->stream_gather = w_bytes > (static_cast<int64_t>(1536) << 20);
+    }
     p->n = static_cast<int>(n);
     {   // floor(x / n) = (t + ((x - t) >> 1)) >> n_shift with t = mulhi(x, n_magic), for all 32-bit x
         int sh = 0;
@@ -1045,7 +1055,7 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     p->key_bits = bits;                                // keys take values 0..L
     p->passes = (bits + kMaxRadixBits - 1) / kMaxRadixBits;
     p->rb = (bits + p->passes - 1) / p->passes;          // digit width, <= 11 bits
-    // Keys of up to 22 bits: split so that a bucket of the high digit holds about 256 pairs (the pairs
+    // Keys of up to 22 bits: split so that a bucket of the high digit holds about kBucketTarget pairs (the pairs
     // spread over the labels), within what the kernels hold: low digit <= 11 bits, and the high digit,
     // with one more value for the masked pairs, < 2^11.
     p->n_buckets = 0; p->low_bits = 0; p->high_rb = 0;
@@ -1103,17 +1113,19 @@ static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, con
                           float* loss_q, float* dZ, int SQ) {
     const float inv_B = 1.0f / static_cast<float>(B);
     const dim3 grid(static_cast<unsigned>(B * SQ));
-#define XC_GATHER2(CPL, UU, FF)                                                                        \
-    XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, UU, FF><<<grid, kStepThreads, 0, st>>>(         \
+#define XC_GATHER2(CPL, UU, FF, SS)                                                                    \
+    XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, UU, FF, SS><<<grid, kStepThreads, 0, st>>>(     \
         static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg,          \
         pl.G, SQ, B, inv_B, keys, vals, gco, loss_q, dZ)))
 #define XC_GATHER(CPL)                                                                                 \
     do {                                                                                               \
         const bool full = (d / Elem<T>::kPerChunk) == pl.G * CPL && d % Elem<T>::kPerChunk == 0;       \
         if (B * SQ <= 1024) {   /* few workgroups: more rows in flight per group */                   \
-            if (full) XC_GATHER2(CPL, 8, true); else XC_GATHER2(CPL, 8, false);                        \
+            if (full) XC_GATHER2(CPL, 8, true, false); else XC_GATHER2(CPL, 8, false, false);          \
+        } else if (full && pl.stream_gather) {                                                         \
+            XC_GATHER2(CPL, 4, true, true);                                                            \
         } else {                                                                                       \
-            if (full) XC_GATHER2(CPL, 4, true); else XC_GATHER2(CPL, 4, false);                        \
+            if (full) XC_GATHER2(CPL, 4, true, false); else XC_GATHER2(CPL, 4, false, false);          \
         }                                                                                              \
     } while (0)
     switch (pl.cpl) {
@@ -1138,11 +1150,13 @@ static void launch_update(const StepPlan& pl, hipStream_t st, const void* Z, voi
     int64_t nwg = (pl.P + NG - 1) / NG;
     if (nwg > kUpdateMaxGrid) nwg = kUpdateMaxGrid;
     const dim3 grid(static_cast<unsigned>(nwg));
-#define XC_UPDATE(CPL)                                                                            \
-    XC_LAUNCH(K_UPDATE, st, (update_kernel<T, CPL><<<grid, kStepThreads,                          \
+#define XC_UPDATE2(CPL, SS)                                                                       \
+    XC_LAUNCH(K_UPDATE, st, (update_kernel<T, CPL, SS><<<grid, kStepThreads,                      \
         kStepThreads * CPL * Elem<T>::kPerChunk * sizeof(float), st>>>(                             \
         static_cast<const T*>(Z), static_cast<T*>(W), d, pl.n_magic, pl.n_shift, pl.G, vals, gco, touched, seg_start, \
         seg_idx0, n_touched, lr, static_cast<T*>(rows_out), dz_part, SQ, BD, dZ)))
+#define XC_UPDATE(CPL)                                                                            \
+    do { if (pl.stream_update) XC_UPDATE2(CPL, true); else XC_UPDATE2(CPL, false); } while (0)
     switch (pl.cpl) {
         case 1: XC_UPDATE(1); break;
         case 2: XC_UPDATE(2); break;
@@ -1150,6 +1164,7 @@ static void launch_update(const StepPlan& pl, hipStream_t st, const void* Z, voi
         default: XC_UPDATE(4); break;
     }
 #undef XC_UPDATE
+#undef XC_UPDATE2
 }
 
 }  // namespace xc

@@ -181,3 +181,24 @@ def test_step_sort_paths(B, L, d, k_p, n_neg, masked):
         neg[m] = np.where(rng.random(int(m.sum())) < 0.5, -1, L + 5).astype(np.int32)
     logq = np.log(rng.uniform(0.05, 1.0, size=(B, n_neg))).astype(np.float32)
     _run_and_check(Z, W, pos, neg, logq, f64(Z), f64(W), 0.2, orc.LOSS_BCE)
+
+
+@pytest.mark.parametrize("dtype,L,d", [
+    (torch.float32, 3_400_000, 128),       # 1.7 GB: the gather and the update both stream the rows
+    (torch.float32, 700_000, 128),         # 0.36 GB: only the update does
+    (torch.bfloat16, 1_500_000, 128),      # 0.38 GB, bf16
+])
+def test_step_on_a_matrix_larger_than_the_last_level_cache(dtype, L, d):
+    """Above 256 MB (update) and 1.5 GB (gather) the rows of W are loaded and stored with the non-temporal
+    hint, in kernel instances of their own: same results."""
+    B, k_p, n_neg = 48, 3, 300
+    rng = np.random.default_rng(L)
+    Z = synth.make_matrix(31, synth.TAG_Z, B, d, dtype, "cuda:0")
+    W = synth.make_matrix(31, synth.TAG_W, L, d, dtype, "cuda:0")
+    pos = np.stack([rng.choice(L, size=k_p, replace=False) for _ in range(B)]).astype(np.int32)
+    neg = rng.integers(0, L, size=(B, n_neg)).astype(np.int32)
+    neg[:, :40] = neg[0, :40]                                # labels shared by every query: long segments
+    neg[rng.random((B, n_neg)) < 0.05] = -1
+    logq = np.log(rng.uniform(0.05, 1.0, size=(B, n_neg))).astype(np.float32)
+    for kind in (orc.LOSS_BCE, orc.LOSS_SOFTMAX):
+        _run_and_check(Z, W, pos, neg, logq, f64(Z), f64(W), 0.2, kind)
