@@ -422,6 +422,21 @@ __device__ __forceinline__ int digit_of(uint32_t key, int shift, int radix, uint
     return key >= inv_key ? inv_digit : static_cast<int>((key >> shift) & static_cast<uint32_t>(radix - 1));
 }
 
+// Sum of v over a workgroup of NW waves, in a fixed order (lanes by butterfly, then waves in turn);
+// every thread gets the total.  `sh` holds NW values and may be reused after the call.
+template <typename V, int NW>
+__device__ __forceinline__ V block_sum(V v, V* sh) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0) sh[threadIdx.x / kWave] = v;
+    __syncthreads();
+    V t = sh[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) t += sh[w];
+    __syncthreads();
+    return t;
+}
+
 __global__ __launch_bounds__(256)
 void radix_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t chunk, int shift, int rb,
                         int nb, int* __restrict__ counts /* [radix][nb] */, uint32_t inv_key, int inv_digit) {
@@ -564,7 +579,7 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
                         int* __restrict__ head_cnt /* [gridDim.x] */) {
     extern __shared__ int sort_lds[];                  // offs[radix], whist[waves][radix]: sized by the launch
     __shared__ int wsum[kSortTile / kWave];
-    __shared__ int red[kSortTile];
+    __shared__ int red[kSortTile / kWave];
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int radix = 1 << rb;
@@ -606,7 +621,6 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
         }
         const int incl = wave_incl_scan(local);
         if ((tid & 63) == 63) wsum[wave] = incl;
-        red[tid] = nz;
         __syncthreads();
         int run = p0 + incl - local;
         for (int w = 0; w < wave; ++w) run += wsum[w];
@@ -614,12 +628,8 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
             const int d = tid * per + j;
             if (d < radix) { offs[d] = run; run += cnt[j]; }
         }
-        for (int s2 = kSortTile / 2; s2 > 0; s2 >>= 1) {
-            __syncthreads();
-            if (tid < s2) red[tid] += red[tid + s2];
-        }
-        __syncthreads();
-        if (tid == 0) head_cnt[b] = red[0];
+        const int heads = block_sum<int, kSortTile / kWave>(nz, red);
+        if (tid == 0) head_cnt[b] = heads;
     }
     if (in_regs) {
 #pragma unroll
@@ -654,7 +664,7 @@ __device__ __forceinline__ bool is_head(const uint32_t* keys, int64_t p, uint32_
 __global__ __launch_bounds__(256)
 void heads_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t chunk, uint32_t Lkey,
                         int* __restrict__ head_cnt, int* __restrict__ valid_cnt) {
-    __shared__ int sh[2][256];
+    __shared__ int sh[4];
     const int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
     p1 = p1 < P ? p1 : P;
@@ -663,13 +673,9 @@ void heads_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
         h += is_head(keys, p, Lkey) ? 1 : 0;
         v += keys[p] < Lkey ? 1 : 0;
     }
-    sh[0][threadIdx.x] = h; sh[1][threadIdx.x] = v;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (static_cast<int>(threadIdx.x) < s) { sh[0][threadIdx.x] += sh[0][threadIdx.x + s]; sh[1][threadIdx.x] += sh[1][threadIdx.x + s]; }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) { head_cnt[blockIdx.x] = sh[0][0]; valid_cnt[blockIdx.x] = sh[1][0]; }
+    h = block_sum<int, 4>(h, sh);
+    v = block_sum<int, 4>(v, sh);
+    if (threadIdx.x == 0) { head_cnt[blockIdx.x] = h; valid_cnt[blockIdx.x] = v; }
 }
 
 __global__ __launch_bounds__(256)
@@ -681,46 +687,33 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
                         float inv_B, float* __restrict__ loss, int SQ,
                         const int* __restrict__ bucket_sizes /* not null: block b covers bucket b ... */,
                         const int* __restrict__ bucket_bases /* ... which starts at pair bucket_bases[b] */) {
-    __shared__ int sh[256];
+    __shared__ int sh[4];
+    __shared__ float shf[4];
     __shared__ int wcnt[4];
     __shared__ int running;
     const int tid = threadIdx.x;
+    if (static_cast<int>(blockIdx.x) == nb) {
+        // one workgroup beyond those of the keys: the totals and the loss, off the other workgroups' path
+        int th = 0, tv = 0;
+        for (int b = tid; b < nb; b += 256) { th += head_cnt[b]; tv += valid_cnt[b]; }
+        th = block_sum<int, 4>(th, sh);
+        tv = block_sum<int, 4>(tv, sh);
+        if (tid == 0) { n_touched[0] = th; seg_start[th] = tv; }
+        // loss = (1/B) sum_i loss_q[i], summed in a fixed order
+        float t2 = 0.0f;
+        for (int64_t i = tid; i < B * SQ; i += 256) t2 += loss_q[i];
+        t2 = block_sum<float, 4>(t2, shf);
+        if (tid == 0) loss[0] = t2 * inv_B;
+        return;
+    }
     int bucket_p0 = 0, bucket_n = 0;
     if (bucket_sizes) { bucket_p0 = bucket_bases[blockIdx.x]; bucket_n = bucket_sizes[blockIdx.x]; }
     // heads in the blocks before this one
     int t = 0;
     for (int b = tid; b < static_cast<int>(blockIdx.x); b += 256) t += head_cnt[b];
-    sh[tid] = t;
+    t = block_sum<int, 4>(t, sh);
+    if (tid == 0) running = t;
     __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if (tid < s) sh[tid] += sh[tid + s];
-        __syncthreads();
-    }
-    if (tid == 0) running = sh[0];
-    __syncthreads();
-    if (blockIdx.x == 0) {             // totals: block 0 sums every block's counts
-        int th = 0, tv = 0;
-        for (int b = tid; b < nb; b += 256) { th += head_cnt[b]; tv += valid_cnt[b]; }
-        __shared__ int sh2[2][256];
-        sh2[0][tid] = th; sh2[1][tid] = tv;
-        __syncthreads();
-        for (int s = 128; s > 0; s >>= 1) {
-            if (tid < s) { sh2[0][tid] += sh2[0][tid + s]; sh2[1][tid] += sh2[1][tid + s]; }
-            __syncthreads();
-        }
-        if (tid == 0) { n_touched[0] = sh2[0][0]; seg_start[sh2[0][0]] = sh2[1][0]; }
-        // loss = (1/B) sum_i loss_q[i], summed in a fixed order
-        __shared__ float shf[256];
-        float t2 = 0.0f;
-        for (int64_t i = tid; i < B * SQ; i += 256) t2 += loss_q[i];
-        shf[tid] = t2;
-        __syncthreads();
-        for (int s = 128; s > 0; s >>= 1) {
-            if (tid < s) shf[tid] += shf[tid + s];
-            __syncthreads();
-        }
-        if (tid == 0) loss[0] = shf[0] * inv_B;
-    }
     int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
     if (bucket_sizes) { p0 = bucket_p0; p1 = p0 + bucket_n; }
@@ -1241,7 +1234,7 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
         XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.high_rb), st>>>(kin, vin, kout, vout, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, totals, Lk, pl.n_buckets, bases)));
         XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, sort_lds_bytes(pl.low_bits), st>>>(kout, vout, kin, vin, totals, bases, pl.low_bits, head_cnt)));
         // the sizes of the label buckets add up to the number of unmasked pairs
-        XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.n_buckets, 256, 0, st>>>(kin, pl.P, pl.chunk, Lk, pl.n_buckets, head_cnt,
+        XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.n_buckets + 1, 256, 0, st>>>(kin, pl.P, pl.chunk, Lk, pl.n_buckets, head_cnt,
                                                                                      totals, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
                                                                                      1.0f / static_cast<float>(B), loss, SQ, totals, bases)));
         XC_HIP_CHECK(hipGetLastError());
@@ -1257,7 +1250,7 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
             uint32_t* tv = vin; vin = vout; vout = tv;
         }
         XC_LAUNCH(K_HEADS_COUNT, st, (heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt)));
-        XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
+        XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.nb + 1, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
                                                                                 valid_cnt, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
                                                                                 1.0f / static_cast<float>(B), loss, SQ, nullptr, nullptr)));
         XC_HIP_CHECK(hipGetLastError());
