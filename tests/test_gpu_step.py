@@ -161,6 +161,9 @@ def test_step_many_long_segments(dtype):
     (96, 700, 64, 4, 300, 0.6),       # most pairs masked (-1 / out of range): they bypass the buckets
     (33, 2, 64, 1, 50, 0.0),          # the smallest label set that takes the bucket path
     (40, 4_300_000, 64, 3, 200, 0.2),  # more labels than 2047 buckets of 2048: digit-by-digit rounds
+    (64, 4_194_303, 16, 2, 300, 0.1),  # 22-bit keys that just miss the split into buckets
+    (50, 30_000_000, 8, 3, 500, 0.3),  # 25-bit keys: three rounds
+    (20, 1, 64, 1, 30, 0.5),           # a single label
 ])
 def test_step_sort_paths(B, L, d, k_p, n_neg, masked):
     """The pair sort behind the row update: bucket sizes far above and below a workgroup's tile,
@@ -202,3 +205,17 @@ def test_step_on_a_matrix_larger_than_the_last_level_cache(dtype, L, d):
     logq = np.log(rng.uniform(0.05, 1.0, size=(B, n_neg))).astype(np.float32)
     for kind in (orc.LOSS_BCE, orc.LOSS_SOFTMAX):
         _run_and_check(Z, W, pos, neg, logq, f64(Z), f64(W), 0.2, kind)
+
+
+def test_step_wide_keys_in_a_narrow_label_range():
+    """25-bit keys whose labels all fall into a narrow range (and a few at the far end): most digit values of the
+    upper rounds are empty and a few hold everything."""
+    B, L, d, k_p, n_neg = 600, 30_000_000, 8, 2, 700
+    rng = np.random.default_rng(77)
+    Z = synth.make_matrix(23, synth.TAG_Z, B, d, torch.float32, "cuda:0")
+    W = synth.make_matrix(23, synth.TAG_W, L, d, torch.float32, "cuda:0")
+    pos = np.stack([rng.choice(100_000, size=k_p, replace=False) for _ in range(B)]).astype(np.int32) + 7_000_000
+    neg = (rng.integers(0, 100_000, size=(B, n_neg)) + 7_000_000).astype(np.int32)
+    neg[:, -5:] = L - 1 - np.arange(5)                       # and a few at the far end of the label range
+    logq = np.log(rng.uniform(0.05, 1.0, size=(B, n_neg))).astype(np.float32)
+    _run_and_check(Z, W, pos, neg, logq, f64(Z), f64(W), 0.2, orc.LOSS_BCE)
