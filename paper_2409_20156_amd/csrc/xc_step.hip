@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kStepThreads)
 void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, int d,
                    const int32_t* __restrict__ pos, int k_p, const int32_t* __restrict__ neg,
                    const float* __restrict__ logq, int n_neg, int G, int SQ, int64_t B, float inv_B,
-                   uint32_t* __restrict__ keys, uint32_t* __restrict__ vals,
+                   uint2* __restrict__ pairs /* (sort key, pair index) */,
                    float* __restrict__ gco, float* __restrict__ loss_q, float* __restrict__ dZ) {
     constexpr int EPC = Elem<T>::kPerChunk;       // U = candidate rows in flight per group
     __shared__ float red[kStepThreads / kWave][kMaxRowFloats];
@@ -320,8 +320,8 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
             float park = g;         // soft-max: the logit is parked until the normaliser is known
             if (KIND == XC_LOSS_SOFTMAX) park = __shfl(my_t, src, kWave);
             if (gl == 0 && c < n) {
-                keys[p_base + c] = ok[u] ? static_cast<uint32_t>(id[u]) : static_cast<uint32_t>(L);
-                vals[p_base + c] = static_cast<uint32_t>(p_base + c);
+                pairs[p_base + c] = make_uint2(ok[u] ? static_cast<uint32_t>(id[u]) : static_cast<uint32_t>(L),
+                                               static_cast<uint32_t>(p_base + c));
                 gco[p_base + c] = park;
             }
         }
@@ -395,8 +395,8 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
         // pair coefficients now that the normaliser is known
         for (int c = tid; c < n; c += kStepThreads) {
             const int64_t p = p_base + c;
-            if (npos_all == 0) { keys[p] = static_cast<uint32_t>(L); gco[p] = 0.0f; }
-            else if (keys[p] != static_cast<uint32_t>(L)) {
+            if (npos_all == 0) { pairs[p].x = static_cast<uint32_t>(L); gco[p] = 0.0f; }
+            else if (pairs[p].x != static_cast<uint32_t>(L)) {
                 const float t = gco[p];
                 gco[p] = (expf(t - lse) - (c < k_p ? inv_npos : 0.0f)) * inv_B;
             }
@@ -438,7 +438,7 @@ __device__ __forceinline__ V block_sum(V v, V* sh) {
 }
 
 __global__ __launch_bounds__(256)
-void radix_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t chunk, int shift, int rb,
+void radix_count_kernel(const uint2* __restrict__ pairs, int64_t P, int64_t chunk, int shift, int rb,
                         int nb, int* __restrict__ counts /* [radix][nb] */, uint32_t inv_key, int inv_digit) {
     __shared__ int hist[kMaxRadix];
     const int radix = 1 << rb;
@@ -448,7 +448,7 @@ void radix_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
     int64_t p1 = p0 + chunk;
     p1 = p1 < P ? p1 : P;
     for (int64_t p = p0 + threadIdx.x; p < p1; p += 256)
-        atomicAdd(&hist[digit_of(keys[p], shift, radix, inv_key, inv_digit)], 1);
+        atomicAdd(&hist[digit_of(pairs[p].x, shift, radix, inv_key, inv_digit)], 1);
     __syncthreads();
     for (int d = threadIdx.x; d < radix; d += 256) counts[d * nb + blockIdx.x] = hist[d];
 }
@@ -473,7 +473,7 @@ void radix_prefix_kernel(int* __restrict__ counts /* [radix][nb], in place */, i
 // the tile's keys of the same digit, and offs moves on.  whist must be zero on entry and is zero on exit.
 __device__ __forceinline__ void place_tile(bool valid, uint32_t key, uint32_t val, int digit, int rb,
                                            int* offs /* [radix] */, int* whist /* [waves][radix] */,
-                                           uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out) {
+                                           uint2* __restrict__ out) {
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int radix = 1 << rb;
@@ -490,8 +490,7 @@ __device__ __forceinline__ void place_tile(bool valid, uint32_t key, uint32_t va
     if (valid) {
         int before = offs[digit];
         for (int w = 0; w < wave; ++w) before += whist[w * radix + digit];
-        keys_out[before + rank] = key;
-        vals_out[before + rank] = val;
+        out[before + rank] = make_uint2(key, val);       // one 8-byte store: key and payload share a line
     }
     lds_barrier();
     // only digits present in this tile need their running offset advanced
@@ -511,8 +510,7 @@ __device__ __forceinline__ void place_tile(bool valid, uint32_t key, uint32_t va
 }
 
 __global__ __launch_bounds__(kSortTile)
-void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
-                          uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, int64_t P,
+void radix_scatter_kernel(const uint2* __restrict__ in, uint2* __restrict__ out, int64_t P,
                           int64_t chunk, int shift, int rb, int nb, const int* __restrict__ prefix,
                           const int* __restrict__ totals, uint32_t inv_key, int inv_digit,
                           int* __restrict__ bases_out /* [radix] or null: where each digit's pairs start */) {
@@ -551,13 +549,13 @@ void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* 
     p1 = p1 < P ? p1 : P;
     // the next tile's pairs are fetched while the current tile is placed
     uint32_t key_n = 0, val_n = 0;
-    if (p0 + tid < p1) { key_n = keys_in[p0 + tid]; val_n = vals_in[p0 + tid]; }
+    if (p0 + tid < p1) { const uint2 kv = in[p0 + tid]; key_n = kv.x; val_n = kv.y; }
     for (int64_t t0 = p0; t0 < p1; t0 += kSortTile) {
         const bool valid = t0 + tid < p1;
         const uint32_t key = key_n, val = val_n;
         const int64_t pn = t0 + kSortTile + tid;
-        if (pn < p1) { key_n = keys_in[pn]; val_n = vals_in[pn]; }
-        place_tile(valid, key, val, digit_of(key, shift, radix, inv_key, inv_digit), rb, offs, whist, keys_out, vals_out);
+        if (pn < p1) { const uint2 kv = in[pn]; key_n = kv.x; val_n = kv.y; }
+        place_tile(valid, key, val, digit_of(key, shift, radix, inv_key, inv_digit), rb, offs, whist, out);
     }
 }
 
@@ -572,8 +570,7 @@ constexpr int kBucketRegTiles = 8;
 constexpr int64_t kBucketTarget = XC_BUCKET_TARGET;   // pairs per bucket the digit split aims at
 
 __global__ __launch_bounds__(kSortTile)
-void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
-                        uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out,
+void bucket_sort_kernel(const uint2* __restrict__ in, uint2* __restrict__ out,
                         const int* __restrict__ sizes /* [gridDim.x] pairs per bucket */,
                         const int* __restrict__ bases /* [gridDim.x] first pair of each bucket */, int rb,
                         int* __restrict__ head_cnt /* [gridDim.x] */) {
@@ -601,13 +598,13 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
         for (int u = 0; u < kBucketRegTiles; ++u) {
             const int p = p0 + u * kSortTile + tid;
             rk[u] = 0; rv[u] = 0;
-            if (p < p1) { rk[u] = keys_in[p]; rv[u] = vals_in[p]; }
+            if (p < p1) { const uint2 kv = in[p]; rk[u] = kv.x; rv[u] = kv.y; }
         }
 #pragma unroll
         for (int u = 0; u < kBucketRegTiles; ++u)
             if (p0 + u * kSortTile + tid < p1) atomicAdd(&offs[rk[u] & static_cast<uint32_t>(radix - 1)], 1);
     } else {
-        for (int p = p0 + tid; p < p1; p += kSortTile) atomicAdd(&offs[keys_in[p] & static_cast<uint32_t>(radix - 1)], 1);
+        for (int p = p0 + tid; p < p1; p += kSortTile) atomicAdd(&offs[in[p].x & static_cast<uint32_t>(radix - 1)], 1);
     }
     __syncthreads();
     {   // bins -> start positions (exclusive scan, contiguous bins per thread); heads = non-empty bins
@@ -637,18 +634,18 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
             if (p0 + u * kSortTile >= p1) break;                       // uniform
             const bool valid = p0 + u * kSortTile + tid < p1;
             place_tile(valid, rk[u], rv[u], static_cast<int>(rk[u] & static_cast<uint32_t>(radix - 1)), rb, offs, whist,
-                       keys_out, vals_out);
+                       out);
         }
     } else {
         uint32_t key_n = 0, val_n = 0;
-        if (p0 + tid < p1) { key_n = keys_in[p0 + tid]; val_n = vals_in[p0 + tid]; }
+        if (p0 + tid < p1) { const uint2 kv = in[p0 + tid]; key_n = kv.x; val_n = kv.y; }
         for (int t0 = p0; t0 < p1; t0 += kSortTile) {
             const bool valid = t0 + tid < p1;
             const uint32_t key = key_n, val = val_n;
             const int pn = t0 + kSortTile + tid;
-            if (pn < p1) { key_n = keys_in[pn]; val_n = vals_in[pn]; }
+            if (pn < p1) { const uint2 kv = in[pn]; key_n = kv.x; val_n = kv.y; }
             place_tile(valid, key, val, static_cast<int>(key & static_cast<uint32_t>(radix - 1)), rb, offs, whist,
-                       keys_out, vals_out);
+                       out);
         }
     }
 }
@@ -656,13 +653,13 @@ void bucket_sort_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __
 // ---------------------------------------------------------------------------
 // segment heads of the sorted keys -> touched list and segment starts
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ bool is_head(const uint32_t* keys, int64_t p, uint32_t Lkey) {
-    const uint32_t k = keys[p];
-    return k < Lkey && (p == 0 || keys[p - 1] != k);
+__device__ __forceinline__ bool is_head(const uint2* pairs, int64_t p, uint32_t Lkey) {
+    const uint32_t k = pairs[p].x;
+    return k < Lkey && (p == 0 || pairs[p - 1].x != k);
 }
 
 __global__ __launch_bounds__(256)
-void heads_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t chunk, uint32_t Lkey,
+void heads_count_kernel(const uint2* __restrict__ pairs, int64_t P, int64_t chunk, uint32_t Lkey,
                         int* __restrict__ head_cnt, int* __restrict__ valid_cnt) {
     __shared__ int sh[4];
     const int64_t p0 = blockIdx.x * chunk;
@@ -670,8 +667,8 @@ void heads_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
     p1 = p1 < P ? p1 : P;
     int h = 0, v = 0;
     for (int64_t p = p0 + threadIdx.x; p < p1; p += 256) {
-        h += is_head(keys, p, Lkey) ? 1 : 0;
-        v += keys[p] < Lkey ? 1 : 0;
+        h += is_head(pairs, p, Lkey) ? 1 : 0;
+        v += pairs[p].x < Lkey ? 1 : 0;
     }
     h = block_sum<int, 4>(h, sh);
     v = block_sum<int, 4>(v, sh);
@@ -679,9 +676,9 @@ void heads_count_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
 }
 
 __global__ __launch_bounds__(256)
-void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t chunk, uint32_t Lkey,
+void heads_write_kernel(const uint2* __restrict__ pairs, int64_t P, int64_t chunk, uint32_t Lkey,
                         int nb, const int* __restrict__ head_cnt, const int* __restrict__ valid_cnt,
-                        const uint32_t* __restrict__ vals, int32_t* __restrict__ touched,
+                        int32_t* __restrict__ touched,
                         int32_t* __restrict__ seg_start, uint32_t* __restrict__ seg_idx0,
                         int32_t* __restrict__ n_touched, const float* __restrict__ loss_q, int64_t B,
                         float inv_B, float* __restrict__ loss, int SQ,
@@ -720,7 +717,7 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
     p1 = p1 < P ? p1 : P;
     for (int64_t t0 = p0; t0 < p1; t0 += 256) {
         const int64_t p = t0 + tid;
-        const bool head = p < p1 && is_head(keys, p, Lkey);
+        const bool head = p < p1 && is_head(pairs, p, Lkey);
         const uint64_t bal = __ballot(head);
         if ((tid & 63) == 0) wcnt[tid >> 6] = __popcll(bal);
         lds_barrier();
@@ -728,9 +725,10 @@ void heads_write_kernel(const uint32_t* __restrict__ keys, int64_t P, int64_t ch
         for (int w = 0; w < (tid >> 6); ++w) before += wcnt[w];
         if (head) {
             const int s = before + __popcll(bal & lanemask_lt());
-            touched[s] = static_cast<int32_t>(keys[p]);
+            const uint2 kv = pairs[p];
+            touched[s] = static_cast<int32_t>(kv.x);
             seg_start[s] = static_cast<int32_t>(p);
-            seg_idx0[s] = vals[p];               // first pair of the segment, saves the update a hop
+            seg_idx0[s] = kv.y;                  // first pair of the segment, saves the update a hop
         }
         lds_barrier();
         if (tid == 0) running += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
@@ -751,7 +749,7 @@ constexpr int kMaxLong = 32;        // queued long segments per workgroup (more 
 template <typename T, int CPL, bool STREAM>
 __global__ __launch_bounds__(kStepThreads)
 void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n_magic, int n_shift, int G,
-                   const uint32_t* __restrict__ vals, const float* __restrict__ gco,
+                   const uint2* __restrict__ pairs, const float* __restrict__ gco,
                    const int32_t* __restrict__ touched, const int32_t* __restrict__ seg_start,
                    const uint32_t* __restrict__ seg_idx0, const int32_t* __restrict__ n_touched, float lr,
                    T* __restrict__ rows_out,
@@ -857,7 +855,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
         float my_g = 0.0f;
         int64_t my_q = 0;
         if (gl < nb) {
-            const uint32_t idx = vals[pb + gl];
+            const uint32_t idx = pairs[pb + gl].y;
             my_g = gco[idx];
             my_q = query_of(idx);
         }
@@ -925,7 +923,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
             float my_g = 0.0f;
             int64_t my_q = 0;
             if (pm < p1) {
-                const uint32_t idx = vals[pm];
+                const uint32_t idx = pairs[pm].y;
                 my_g = gco[idx];
                 my_q = query_of(idx);
             }
@@ -1006,7 +1004,7 @@ struct StepPlan {
     bool stream_update, stream_gather;      // rows of W go through the caches with the non-temporal hint
     uint32_t n_magic;
     int64_t chunk;
-    size_t off_keys0, off_keys1, off_vals0, off_vals1, off_g, off_lossq, off_dzpart, off_counts, off_totals, off_bases, off_headcnt,
+    size_t off_pairs0, off_pairs1, off_g, off_lossq, off_dzpart, off_counts, off_totals, off_bases, off_headcnt,
         off_validcnt, off_segstart, off_segidx0, total;
 };
 
@@ -1081,8 +1079,7 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     size_t off = 0;
     auto take = [&off](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
     const size_t P = static_cast<size_t>(p->P);
-    p->off_keys0 = take(P * 4); p->off_keys1 = take(P * 4);
-    p->off_vals0 = take(P * 4); p->off_vals1 = take(P * 4);
+    p->off_pairs0 = take(P * 8); p->off_pairs1 = take(P * 8);
     p->off_g = take(P * 4);
     // few queries: several workgroups share a query so that the chip is filled
     p->sq = B >= 1536 ? 1 : (B >= 768 ? 2 : 4);
@@ -1102,14 +1099,14 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
 template <typename T, int KIND>
 static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, const void* W, int64_t B,
                           int64_t L, int d, const int32_t* pos, int k_p, const int32_t* neg,
-                          const float* logq, int n_neg, uint32_t* keys, uint32_t* vals, float* gco,
+                          const float* logq, int n_neg, uint2* pairs, float* gco,
                           float* loss_q, float* dZ, int SQ) {
     const float inv_B = 1.0f / static_cast<float>(B);
     const dim3 grid(static_cast<unsigned>(B * SQ));
 #define XC_GATHER2(CPL, UU, FF, SS)                                                                    \
     XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, UU, FF, SS><<<grid, kStepThreads, 0, st>>>(     \
         static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg,          \
-        pl.G, SQ, B, inv_B, keys, vals, gco, loss_q, dZ)))
+        pl.G, SQ, B, inv_B, pairs, gco, loss_q, dZ)))
 #define XC_GATHER(CPL)                                                                                 \
     do {                                                                                               \
         const bool full = (d / Elem<T>::kPerChunk) == pl.G * CPL && d % Elem<T>::kPerChunk == 0;       \
@@ -1133,7 +1130,7 @@ static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, con
 
 template <typename T>
 static void launch_update(const StepPlan& pl, hipStream_t st, const void* Z, void* W, int d,
-                          const uint32_t* vals, const float* gco, const int32_t* touched,
+                          const uint2* pairs, const float* gco, const int32_t* touched,
                           const int32_t* seg_start, const uint32_t* seg_idx0, const int32_t* n_touched,
                           float lr, void* rows_out,
                           const float* dz_part, int SQ, int64_t BD, float* dZ) {
@@ -1146,7 +1143,7 @@ static void launch_update(const StepPlan& pl, hipStream_t st, const void* Z, voi
 #define XC_UPDATE2(CPL, SS)                                                                       \
     XC_LAUNCH(K_UPDATE, st, (update_kernel<T, CPL, SS><<<grid, kStepThreads,                      \
         kStepThreads * CPL * Elem<T>::kPerChunk * sizeof(float), st>>>(                             \
-        static_cast<const T*>(Z), static_cast<T*>(W), d, pl.n_magic, pl.n_shift, pl.G, vals, gco, touched, seg_start, \
+        static_cast<const T*>(Z), static_cast<T*>(W), d, pl.n_magic, pl.n_shift, pl.G, pairs, gco, touched, seg_start, \
         seg_idx0, n_touched, lr, static_cast<T*>(rows_out), dz_part, SQ, BD, dZ)))
 #define XC_UPDATE(CPL)                                                                            \
     do { if (pl.stream_update) XC_UPDATE2(CPL, true); else XC_UPDATE2(CPL, false); } while (0)
@@ -1193,10 +1190,8 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     unsigned char* w8 = static_cast<unsigned char*>(ws);
-    uint32_t* keys0 = reinterpret_cast<uint32_t*>(w8 + pl.off_keys0);
-    uint32_t* keys1 = reinterpret_cast<uint32_t*>(w8 + pl.off_keys1);
-    uint32_t* vals0 = reinterpret_cast<uint32_t*>(w8 + pl.off_vals0);
-    uint32_t* vals1 = reinterpret_cast<uint32_t*>(w8 + pl.off_vals1);
+    uint2* pairs0 = reinterpret_cast<uint2*>(w8 + pl.off_pairs0);
+    uint2* pairs1 = reinterpret_cast<uint2*>(w8 + pl.off_pairs1);
     float* gco = reinterpret_cast<float*>(w8 + pl.off_g);
     float* loss_q = reinterpret_cast<float*>(w8 + pl.off_lossq);
     int* counts = reinterpret_cast<int*>(w8 + pl.off_counts);
@@ -1212,30 +1207,30 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
     float* dz_target = SQ > 1 ? reinterpret_cast<float*>(w8 + pl.off_dzpart) : dZ;
     if (t == XC_BF16) {
         if (kind == XC_LOSS_BCE)
-            launch_gather<bf16_t, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dz_target, SQ);
+            launch_gather<bf16_t, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, pairs0, gco, loss_q, dz_target, SQ);
         else
-            launch_gather<bf16_t, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dz_target, SQ);
+            launch_gather<bf16_t, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, pairs0, gco, loss_q, dz_target, SQ);
     } else {
         if (kind == XC_LOSS_BCE)
-            launch_gather<float, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dz_target, SQ);
+            launch_gather<float, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, pairs0, gco, loss_q, dz_target, SQ);
         else
-            launch_gather<float, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, keys0, vals0, gco, loss_q, dz_target, SQ);
+            launch_gather<float, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, pairs0, gco, loss_q, dz_target, SQ);
     }
     XC_HIP_CHECK(hipGetLastError());
 
     // S5: sort pairs by label
-    uint32_t *kin = keys0, *kout = keys1, *vin = vals0, *vout = vals1;
+    uint2 *kin = pairs0, *kout = pairs1;
     if (pl.n_buckets > 0) {
         // one round on the high digit (masked pairs behind every label), then each bucket by its low digit
         const int radix = 1 << pl.high_rb;
         const uint32_t Lk = static_cast<uint32_t>(L);
         XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, Lk, pl.n_buckets)));
         XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
-        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.high_rb), st>>>(kin, vin, kout, vout, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, totals, Lk, pl.n_buckets, bases)));
-        XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, sort_lds_bytes(pl.low_bits), st>>>(kout, vout, kin, vin, totals, bases, pl.low_bits, head_cnt)));
+        XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.high_rb), st>>>(kin, kout, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, totals, Lk, pl.n_buckets, bases)));
+        XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, sort_lds_bytes(pl.low_bits), st>>>(kout, kin, totals, bases, pl.low_bits, head_cnt)));
         // the sizes of the label buckets add up to the number of unmasked pairs
         XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.n_buckets + 1, 256, 0, st>>>(kin, pl.P, pl.chunk, Lk, pl.n_buckets, head_cnt,
-                                                                                     totals, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
+                                                                                     totals, touched, seg_start, seg_idx0, n_touched, loss_q, B,
                                                                                      1.0f / static_cast<float>(B), loss, SQ, totals, bases)));
         XC_HIP_CHECK(hipGetLastError());
     } else {
@@ -1244,19 +1239,18 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
             const int radix = 1 << pl.rb;
             XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, 0xffffffffu, 0)));
             XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
-            XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.rb), st>>>(kin, vin, kout, vout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals, 0xffffffffu, 0, nullptr)));
+            XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.rb), st>>>(kin, kout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals, 0xffffffffu, 0, nullptr)));
             XC_HIP_CHECK(hipGetLastError());
-            uint32_t* tk = kin; kin = kout; kout = tk;
-            uint32_t* tv = vin; vin = vout; vout = tv;
+            uint2* tk = kin; kin = kout; kout = tk;
         }
         XC_LAUNCH(K_HEADS_COUNT, st, (heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt)));
         XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.nb + 1, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
-                                                                                valid_cnt, vin, touched, seg_start, seg_idx0, n_touched, loss_q, B,
+                                                                                valid_cnt, touched, seg_start, seg_idx0, n_touched, loss_q, B,
                                                                                 1.0f / static_cast<float>(B), loss, SQ, nullptr, nullptr)));
         XC_HIP_CHECK(hipGetLastError());
     }
-    if (t == XC_BF16) launch_update<bf16_t>(pl, st, Z, W, d, vin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
-    else launch_update<float>(pl, st, Z, W, d, vin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
+    if (t == XC_BF16) launch_update<bf16_t>(pl, st, Z, W, d, kin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
+    else launch_update<float>(pl, st, Z, W, d, kin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
     XC_HIP_CHECK(hipGetLastError());
     return XC_OK;
 }
