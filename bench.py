@@ -107,16 +107,19 @@ class Job:
         return b
 
 
-def cpu_baseline(wl, pool, budget_queries=32):
-    """The oracle as it stands on a bounded sample: mining of `budget_queries`
-    queries against all L labels (scaled to the pool), and sampling + step of the
-    first `nb` queries of a batch (scaled to B)."""
+def cpu_baseline(wl, pool, budget_queries=None):
+    """The oracle as it stands on a bounded sample of 10-20 s of CPU work: mining of
+    `budget_queries` queries against all L labels (as many as keep the score matrix
+    within 1 GiB, at most 1024; scaled to the pool), and sampling + step of the first
+    `nb` queries of a batch (scaled to B)."""
     import numpy as np
     import torch
 
     from oracle import astra_oracle as orc
     from paper_2409_20156_amd import synth
-    nb = min(wl.B, 64)
+    nb = min(wl.B, 512)
+    if budget_queries is None:
+        budget_queries = max(8, min(1024, (1 << 27) // wl.L))
     W = synth.make_matrix(synth.BASE_SEED, synth.TAG_W, wl.L, wl.d, wl.torch_dtype, "cpu").to(torch.float64).numpy()
     Z = synth.make_matrix(synth.BASE_SEED, synth.TAG_Z, max(nb, budget_queries), wl.d, wl.torch_dtype, "cpu").to(torch.float64).numpy()
     pos = synth.zipf_positives(synth.BASE_SEED, nb, wl.L, wl.zipf_s, wl.count_law, wl.k_p)
