@@ -39,7 +39,7 @@ def short_name(full: str):
     return KERNELS.get(fn, fn)
 
 
-def stats(src, out, title, cmd):
+def stats(src, out, title, cmd, trace=None):
     rows = list(csv.DictReader(open(src)))
     agg = defaultdict(lambda: [0, 0, 1 << 62, 0, 0.0])
     for r in rows:
@@ -60,6 +60,40 @@ def stats(src, out, title, cmd):
         for n, a in sorted(agg.items(), key=lambda kv: -kv[1][1]):
             f.write("| %s | %d | %.3f | %.2f | %.2f | %.2f | %.2f |\n"
                     % (n, a[0], a[1] / 1e6, a[1] / a[0] / 1e3, a[2] / 1e3, a[3] / 1e3, a[4]))
+        if trace:
+            f.write(_searches(trace))
+
+
+def _searches(trace):
+    """The mine_tile launches of the trace grouped into searches (a run of mining kernels between other
+    kernels of the library).  A search from scratch is four sweeps; a warm one is one sweep and four launches
+    that return at once, and its mean per launch is the figure bench.py reports as the kernel's average."""
+    rows = [r for r in csv.DictReader(open(trace)) if short_name(r["Kernel_Name"]) is not None]
+    rows.sort(key=lambda r: int(r["Start_Timestamp"]))
+    groups, cur = [], []
+    for r in rows:
+        n = short_name(r["Kernel_Name"])
+        if n.startswith("mine_"):
+            if n == "mine_tile":
+                cur.append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+        elif n not in ("copy_probe", "mfma_probe"):
+            if cur:
+                groups.append(cur)
+            cur = []
+    if cur:
+        groups.append(cur)
+    by = defaultdict(list)
+    for g in groups:
+        by[len(g)].append(g)
+    out = ["\nmine_tile launches grouped by search (one search = the mining kernels between two steps; four launches: a "
+           "search from scratch; five: a search started from the previous thresholds, whose mean per launch is what "
+           "`bench.py` reports as `roofline.avg_us` from its own HIP events):\n\n",
+           "| launches per search | searches | mean total us | mean per launch us | longest launch us |\n|---|---|---|---|---|\n"]
+    for k in sorted(by):
+        gs = by[k]
+        tot = sum(sum(g) for g in gs) / len(gs)
+        out.append("| %d | %d | %.1f | %.1f | %.1f |\n" % (k, len(gs), tot / 1e3, tot / k / 1e3, max(max(g) for g in gs) / 1e3))
+    return "".join(out)
 
 
 def _counter_means(path, counter):
@@ -152,7 +186,7 @@ def sq(src, out, title, cmd):
 
 if __name__ == "__main__":
     if len(sys.argv) >= 2 and sys.argv[1] == "stats":
-        stats(*sys.argv[2:6])
+        stats(*sys.argv[2:7])
     elif len(sys.argv) >= 2 and sys.argv[1] == "pmc":
         pmc(*sys.argv[2:9])
     elif len(sys.argv) >= 2 and sys.argv[1] == "sq":
