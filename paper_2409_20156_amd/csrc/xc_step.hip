@@ -92,8 +92,14 @@ __device__ __forceinline__ float fast_log1p(float e) {
 // Transposing reduction over a group of G lanes: v[u] holds this lane's partial of row u.
 // Returns, in lane gl, the sum over the group of row row_of_lane(gl): U-1 exchanges in the
 // halving steps plus log2(G/U) plain ones, instead of U*log2(G).
+// Value of lane (addr4 / 4) of the wave: one ds_bpermute.  The callers keep 4 * lane in a register and form
+// the address with one XOR or take it from a loop-invariant; __shfl would recompute the lane id, the width
+// arithmetic and the address at every call, which in the gather's inner loop was a tenth of all instructions.
+__device__ __forceinline__ float lane_read(int addr4, float v) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(addr4, __float_as_int(v)));
+}
 template <int U>
-__device__ __forceinline__ float reduce_rows(float (&v)[U], int G, int gl) {
+__device__ __forceinline__ float reduce_rows(float (&v)[U], int G, int gl, int lane4) {
     int off = G >> 1;
 #pragma unroll
     for (int cnt = U; cnt > 1; cnt >>= 1) {
@@ -102,12 +108,12 @@ __device__ __forceinline__ float reduce_rows(float (&v)[U], int G, int gl) {
         for (int j = 0; j < cnt / 2; ++j) {
             const float send = hi ? v[j] : v[j + cnt / 2];
             const float keep = hi ? v[j + cnt / 2] : v[j];
-            v[j] = keep + __shfl_xor(send, off, kWave);
+            v[j] = keep + lane_read(lane4 ^ (off << 2), send);
         }
         off >>= 1;
     }
     float y = v[0];
-    for (; off > 0; off >>= 1) y += __shfl_xor(y, off, kWave);
+    for (; off > 0; off >>= 1) y += lane_read(lane4 ^ (off << 2), y);
     return y;
 }
 template <int U>
@@ -193,20 +199,22 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
 
     // ids and log-proposals of the candidates this group handles in one iteration; those
     // of the next iteration are fetched while the rows of the current one are in flight
+    // The loads are unconditional, from a clamped index, and what they return is looked at only when the
+    // iteration that uses it begins: nothing waits for them where they are issued, behind the row loads.
     int32_t id_nx[U];
     float lq_nx[U];
     auto fetch_ids = [&](int c0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int c = c0 + u * NG;
+            int cn = c0 + u * NG - k_p;
+            cn = cn < 0 ? 0 : cn;
+            cn = cn < n_neg ? cn : n_neg - 1;
             id_nx[u] = -1; lq_nx[u] = 0.0f;
-            if (c < n) {
-                if (c < k_p) id_nx[u] = spos[c];
-                else { id_nx[u] = neg_i[c - k_p]; lq_nx[u] = lq_i[c - k_p]; }
-            }
+            if (n_neg > 0) { id_nx[u] = neg_i[cn]; lq_nx[u] = lq_i[cn]; }      // uniform
         }
     };
     fetch_ids(grp);
+    const int lane4 = lane << 2;
     const int grp_lane0 = lane & ~(G - 1);       // first lane of this group within the wave
     const uint64_t grp_mask = (G == kWave ? ~0ull : ((1ull << G) - 1ull)) << grp_lane0;
     const int row_rep = G / U;                   // lanes that end up holding the same row's score
@@ -222,11 +230,16 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u * NG;
-            id[u] = id_nx[u]; lq[u] = lq_nx[u]; isp[u] = c < k_p;
+            isp[u] = c < k_p;
+            const int32_t idp = spos[c & (XC_MAX_KP - 1)];           // read whatever c is, used if c < k_p
+            id[u] = isp[u] ? idp : (c < n ? id_nx[u] : -1);
+            lq[u] = (!isp[u] && c < n) ? lq_nx[u] : 0.0f;
             ok[u] = id[u] >= 0 && id[u] < L;
-            if (!isp[u]) {                          // (1 - y_l): a positive among the negatives
-                bool hit = my_pos == id[u];
-                for (int q = G + gl; q < k_p; q += G) hit = hit || spos[q] == id[u];
+            {                                       // (1 - y_l): a positive among the negatives
+                bool hit = !isp[u] && my_pos == id[u];
+                if (k_p > G) {                      // uniform: more positives than lanes in a group
+                    for (int q = G + gl; q < k_p; q += G) hit = hit || (!isp[u] && spos[q] == id[u]);
+                }
                 ok[u] = ok[u] && (__ballot(hit) & grp_mask) == 0ull;
             }
             if (FULL) {
@@ -257,7 +270,7 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
             for (int j = 0; j < CPL; ++j) s = Elem<T>::dot(rw[u][j], zp[j], s);
             ps[u] = s;
         }
-        const float my_s = reduce_rows<U>(ps, G, gl);
+        const float my_s = reduce_rows<U>(ps, G, gl, lane4);
         float my_lq = 0.0f;
         bool my_ok = false, my_isp = false;
 #pragma unroll
@@ -281,12 +294,12 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
             }
         } else {
             float mi = my_t;        // maximum logit of the iteration, over the row-selecting lane bits
-            for (int off = G >> 1; off >= row_rep; off >>= 1) mi = fmaxf(mi, __shfl_xor(mi, off, kWave));
+            for (int off = G >> 1; off >= row_rep; off >>= 1) mi = fmaxf(mi, lane_read(lane4 ^ (off << 2), mi));
             const float mn = fmaxf(m_run, mi);
             const float sc_run = rescale(m_run, mn);
             my_g = my_ok ? expf(my_t - mn) : 0.0f;
             float ws = my_g;
-            for (int off = G >> 1; off >= row_rep; off >>= 1) ws += __shfl_xor(ws, off, kWave);
+            for (int off = G >> 1; off >= row_rep; off >>= 1) ws += lane_read(lane4 ^ (off << 2), ws);
             s_run = s_run * sc_run + ws;
             m_run = mn;
             if (my_ok && my_isp && my_rep) { loss_acc += my_t; ++npos; }
@@ -301,7 +314,7 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u * NG;
             const int src = grp_lane0 + lane_of_row<U>(u, G);
-            const float g = __shfl(my_g, src, kWave);    // zero for a masked pair
+            const float g = lane_read(src << 2, my_g);   // zero for a masked pair
             if (FULL || ok[u]) {
                 float wf[CPL][EPC];
 #pragma unroll
@@ -318,7 +331,7 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
                 }
             }
             float park = g;         // soft-max: the logit is parked until the normaliser is known
-            if (KIND == XC_LOSS_SOFTMAX) park = __shfl(my_t, src, kWave);
+            if (KIND == XC_LOSS_SOFTMAX) park = lane_read(src << 2, my_t);
             if (gl == 0 && c < n) {
                 pairs[p_base + c] = make_uint2(ok[u] ? static_cast<uint32_t>(id[u]) : static_cast<uint32_t>(L),
                                                static_cast<uint32_t>(p_base + c));
