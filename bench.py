@@ -2,22 +2,32 @@
 """Throughput of the ASTRA classifier-layer hot path on one MI355X.
 
 One "step" = one pass of the whole hot path over one batch of synthetic input:
-xc_sample_negatives + xc_step, plus, every `refresh` steps, xc_mine_negatives over
-the whole query pool (the shortlist refresh of Alg. 1).  The default workload is
-the second configuration of the baseline file (L=131072, d=768, bf16, B=512,
-k_h=64, k_r=256, refresh every 20 steps, pool of 10240 queries).
+xc_sample_negatives + xc_step, plus the shortlist search of Alg. 1
+(xc_mine_negatives over the whole query pool) whenever the schedule asks for one.
+The timed region is the workload's scripted run: it starts with a search from
+scratch and repeats the search every `refresh` steps (c2: every 20 steps, the
+later ones started from the thresholds of the one before, same result), or, for
+the workloads defined as "one mining pass plus N steps" (c3, c4, c5), once per N
+steps.  So `value` always contains the mining the workload defines.
 
-Prints ONE JSON line.  `value` is queries/s over the timed region with all
-inputs resident in HBM.  `roofline` describes the kernel that takes the most
-time, timed per launch with HIP events on its own stream in a second pass over
-the same steps (so the event records do not perturb `value`).  `cpu_baseline`
-is the CPU oracle timed on a bounded sample of the same workload.
+The default workload is the largest configuration of the baseline file that fits
+one GPU: c5 (L = 120 M labels, d = 256, bf16, about 61 GB of classifier rows,
+B = 4096, one search over 16 384 queries plus 100 steps).  The smaller
+configurations run after it and ride along under `other_workloads`.
+
+Prints ONE JSON line.  `value` is queries/s over the timed region with all inputs
+resident in HBM.  `roofline` describes the kernel that takes the most time of the
+scripted run, timed with HIP events on its own stream in a second pass over the
+same steps (so the event records do not perturb `value`); for the search it is
+per call (the launches of one search summed), for the step kernels per launch.
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -27,33 +37,42 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E
 PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+HEADLINE = "c5"
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", help="tiny, c2, c3, c4 or c5")
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default: the workload's scripted run)")
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=HEADLINE, help="tiny, c2, c3, c4 or c5")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated workloads reported under other_workloads (default: c2,c3,c4 when the "
+                         "headline workload runs with default steps; 'none' for none)")
     ap.add_argument("--pool", type=int, default=0, help="override the mined query pool size")
+    ap.add_argument("--structured", action="store_true",
+                    help="structured variant of the inputs: every query is pulled towards its first positive, so "
+                         "searches return positives (masked in the step) and shortlists overlap")
+    ap.add_argument("--no-structured-line", action="store_true",
+                    help="do not add the structured-variant run of the headline workload under `structured`")
     ap.add_argument("--warm-margin", type=float, default=0.1,
-                    help="refreshes after the first start from the thresholds of the one before, lowered by this "
-                         "relative margin (xc_mine_negatives_warm: same shortlists); negative: every refresh is a full search")
+                    help="searches after the first of a scripted run start from the thresholds of the one before, "
+                         "lowered by this relative margin (xc_mine_negatives_warm: same shortlists); negative: "
+                         "every search is a full search")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch the library's plain copy kernel over this many MiB (three times), "
                          "for scaling hardware traffic counters in rocprofv3 --pmc runs")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
-                    help="measured HBM bytes per launch from rocprofv3 --pmc runs, if present")
+                    help="HBM bytes per launch / per search from rocprofv3 --pmc runs (replayed, not measured here)")
     return ap.parse_args()
 
 
 class Job:
     """Device-resident state of one workload and the step function."""
 
-    def __init__(self, wl, pool, device="cuda:0", warm_margin=None):
-        import numpy as np
+    def __init__(self, wl, pool, device="cuda:0", warm_margin=None, structured=False):
         import torch
 
         import paper_2409_20156_amd as xc
@@ -64,6 +83,8 @@ class Job:
         self.W = synth.make_matrix(synth.BASE_SEED, synth.TAG_W, wl.L, wl.d, wl.torch_dtype, device)
         self.Zpool = synth.make_matrix(synth.BASE_SEED, synth.TAG_Z, pool, wl.d, wl.torch_dtype, device)
         pos = synth.zipf_positives(synth.BASE_SEED, pool, wl.L, wl.zipf_s, wl.count_law, wl.k_p)
+        if structured:
+            self.Zpool = synth.add_positive_signal(self.Zpool, self.W, pos)
         self.pos_np = pos
         self.pos = torch.tensor(pos, device=device)
         self.nbatch = max(1, pool // wl.B)
@@ -82,21 +103,30 @@ class Job:
                     "n_touched": torch.empty(1, dtype=torch.int32, device=device)}
         self.valid_pairs = [int((pos[b * wl.B:(b + 1) * wl.B] >= 0).sum()) + wl.B * n_neg
                             for b in range(self.nbatch)]
-        self.t = 0
-        self.mined = False
+        self.period = wl.refresh if wl.refresh else wl.steps      # steps between two searches
         self.warm_margin = warm_margin
+        self.restart()
 
-    def mine(self):
-        # every refresh after the first starts from the thresholds of the one before (same result)
-        margin = self.warm_margin if self.mined else None
+    def restart(self):
+        """Back to the start of the scripted run (W keeps what the steps so far made of it)."""
+        self.t = 0
+        self.searches = {"cold": 0, "warm": 0}
+
+    def mines_at(self, t):
+        return t % self.period == 0
+
+    def mine(self, t):
+        # the first search of a scripted run is a search from scratch; the later ones of the same run start
+        # from the thresholds of the one before (same result)
+        cold = t % self.wl.steps == 0 or self.warm_margin is None
         self.xc.mine_negatives(self.Zpool, self.W, self.wl.k_h, workspace=self.mine_ws, out=self.shortlist,
-                               warm_margin=margin)
-        self.mined = True
+                               warm_margin=None if cold else self.warm_margin)
+        self.searches["cold" if cold else "warm"] += 1
 
     def step(self):
         wl, t = self.wl, self.t
-        if (wl.refresh and t % wl.refresh == 0) or (not wl.refresh and t == 0):
-            self.mine()
+        if self.mines_at(t):
+            self.mine(t)
         b = t % self.nbatch
         lo, hi = b * wl.B, (b + 1) * wl.B
         seed = self.synth.step_seed(self.synth.BASE_SEED, wl.config_id, t)
@@ -107,42 +137,172 @@ class Job:
         return b
 
 
-def cpu_baseline(wl, pool, budget_queries=None):
-    """The oracle as it stands on a bounded sample of 10-20 s of CPU work: mining of
-    `budget_queries` queries against all L labels (as many as keep the score matrix
-    within 1 GiB, at most 1024; scaled to the pool), and sampling + step of the first
-    `nb` queries of a batch (scaled to B)."""
+def cpu_baseline(wl, pool, steps):
+    """The oracle as it stands on a bounded sample of about 10-30 s of CPU work, scaled to the scripted run.
+
+    Search: `nq` queries against the first `Ls` labels (all of them where the float64 matrix stays below
+    about 4 GB, else a prefix whose rows are generated on the fly), scaled linearly to pool x L.
+    Sampling + step: `nb` queries of a batch, scaled to B; for a label set too large to hold in float64
+    the oracle gets the renumbered sub-problem with exactly the rows these pairs use."""
     import numpy as np
     import torch
 
     from oracle import astra_oracle as orc
     from paper_2409_20156_amd import synth
-    nb = min(wl.B, 512)
-    if budget_queries is None:
-        budget_queries = max(8, min(1024, (1 << 27) // wl.L))
-    W = synth.make_matrix(synth.BASE_SEED, synth.TAG_W, wl.L, wl.d, wl.torch_dtype, "cpu").to(torch.float64).numpy()
-    Z = synth.make_matrix(synth.BASE_SEED, synth.TAG_Z, max(nb, budget_queries), wl.d, wl.torch_dtype, "cpu").to(torch.float64).numpy()
+    nb = min(wl.B, 256 if wl.L * wl.d > (1 << 29) else 512)
+    Ls = min(wl.L, (1 << 29) // wl.d)                               # at most 4 GiB of float64
+    nq = max(8, min(1024, (1 << 27) // Ls))
+    W = synth.make_matrix(synth.BASE_SEED, synth.TAG_W, Ls, wl.d, wl.torch_dtype, "cpu").to(torch.float64).numpy()
+    Z = synth.make_matrix(synth.BASE_SEED, synth.TAG_Z, max(nb, nq), wl.d, wl.torch_dtype, "cpu").to(torch.float64).numpy()
     pos = synth.zipf_positives(synth.BASE_SEED, nb, wl.L, wl.zipf_s, wl.count_law, wl.k_p)
     t0 = time.perf_counter()
-    sl, _ = orc.mine_negatives(Z[:budget_queries], W, wl.k_h)
-    t_mine_q = (time.perf_counter() - t0) / budget_queries
-    sl_b = sl[:nb] if budget_queries >= nb else orc.mine_negatives(Z[:nb], W, wl.k_h)[0]
-    t0 = time.perf_counter()
-    neg, logq = orc.sample_negatives(sl_b, nb, wl.k_h, wl.k_r, wl.L, 1)
-    orc.xc_step(Z[:nb], W, pos, neg, logq, wl.lr, storage=wl.dtype)
-    t_step_q = (time.perf_counter() - t0) / nb
-    refresh = wl.refresh if wl.refresh else wl.steps
-    per_query = t_step_q + t_mine_q * pool / (refresh * wl.B)
+    sl, _ = orc.mine_negatives(Z[:nq], W, wl.k_h)
+    t_mine_pair = (time.perf_counter() - t0) / (nq * Ls)             # seconds per (query, label)
+    if Ls == wl.L:
+        sl_b = sl[:nb] if nq >= nb else orc.mine_negatives(Z[:nb], W, wl.k_h)[0]
+        t0 = time.perf_counter()
+        neg, logq = orc.sample_negatives(sl_b, nb, wl.k_h, wl.k_r, wl.L, 1)
+        orc.xc_step(Z[:nb], W, pos, neg, logq, wl.lr, storage=wl.dtype)
+        t_step_q = (time.perf_counter() - t0) / nb
+    else:
+        # a shortlist over the whole label range (any distinct ids serve the timing), then the rows in use
+        del W
+        rng = np.random.default_rng(5)
+        sl_b = np.stack([rng.choice(wl.L, size=wl.k_h, replace=False) for _ in range(nb)]).astype(np.int32)
+        t0 = time.perf_counter()
+        neg, logq = orc.sample_negatives(sl_b, nb, wl.k_h, wl.k_r, wl.L, 1)
+        t_sample = time.perf_counter() - t0
+        p64, n64 = pos.astype(np.int64), neg.astype(np.int64)
+        used = np.unique(np.concatenate([p64[p64 >= 0], n64.reshape(-1)]))
+        rows = synth.gaussian_rows_at(synth.BASE_SEED, synth.TAG_W, torch.as_tensor(used), wl.d,
+                                      wl.torch_dtype).to(torch.float64).numpy()
+        pos_c = np.where(p64 >= 0, np.searchsorted(used, np.maximum(p64, 0)), -1).astype(np.int32)
+        neg_c = np.searchsorted(used, n64).astype(np.int32)
+        t0 = time.perf_counter()
+        orc.xc_step(Z[:nb], rows, pos_c, neg_c, logq, wl.lr, storage=wl.dtype)
+        t_step_q = (t_sample + time.perf_counter() - t0) / nb
+    period = wl.refresh if wl.refresh else wl.steps
+    per_query = t_step_q + t_mine_pair * wl.L * pool / (period * wl.B)
     try:
         import threadpoolctl
         cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
     return {"value": 1.0 / per_query, "unit": "queries/s", "cores": cores, "kind": "oracle",
-            "sample": "mining %d queries x all %d labels scaled to the pool of %d per %d steps; "
-                      "sampling+step on %d queries scaled to B=%d; numpy float64 oracle, BLAS threads = cores"
-                      % (budget_queries, wl.L, pool, refresh, nb, wl.B),
-            "mine_s_per_query": t_mine_q, "step_s_per_query": t_step_q}
+            "sample": "search: %d queries x the first %d of %d labels, scaled linearly to the pool of %d queries x all "
+                      "labels, one search per %d steps (extrapolated); sampling + step: %d queries of a batch%s, "
+                      "scaled to B=%d; numpy float64 oracle, BLAS threads = cores"
+                      % (nq, Ls, wl.L, pool, period, nb,
+                         "" if Ls == wl.L else " on the renumbered sub-problem holding the rows their pairs use", wl.B),
+            "mine_s_per_query_label": t_mine_pair, "step_s_per_query": t_step_q}
+
+
+def _traffic(path, wl_name):
+    """Replayed, not measured in this run: bytes per launch (per search for the tile kernel) from the committed
+    rocprofv3 --pmc summaries, with the commit that last changed the file."""
+    if not os.path.exists(path):
+        return {}, None
+    try:
+        data = json.load(open(path)).get(wl_name, {})
+    except Exception:
+        return {}, None
+    commit = None
+    try:
+        commit = subprocess.run(["git", "-C", ROOT, "log", "-1", "--format=%h", "--", path], capture_output=True,
+                                text=True, timeout=10).stdout.strip() or None
+    except Exception:
+        pass
+    return data, {"file": os.path.relpath(path, ROOT), "commit": commit, "replayed": True}
+
+
+def run_workload(args, name, steps=0, warmup=None, structured=False, profile_pass=True):
+    """Warm-up, the timed scripted run, and (optionally) the same run again with per-kernel events."""
+    import torch
+
+    from paper_2409_20156_amd import binding, synth
+    wl = synth.WORKLOADS[name]
+    pool = args.pool or wl.pool
+    K = steps or wl.steps
+    W_ = args.warmup if warmup is None else warmup
+    job = Job(wl, pool, warm_margin=args.warm_margin if args.warm_margin >= 0 else None, structured=structured)
+    torch.cuda.synchronize()
+
+    for _ in range(W_):                       # includes one search (step 0 of a scripted run)
+        job.step()
+    torch.cuda.synchronize()
+    job.restart()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        job.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    res = {"workload": "%s: L=%d d=%d %s B=%d k_p<=%d k_h=%d k_r=%d pool=%d, one search per %d steps%s"
+                       % (wl.name, wl.L, wl.d, wl.dtype, wl.B, wl.k_p, wl.k_h, wl.k_r, pool, job.period,
+                          ", structured inputs" if structured else ""),
+           "value": wl.B * K / elapsed, "unit": "queries/s", "steps": K, "warmup": W_,
+           "ms_per_step": elapsed * 1e3 / K, "searches_in_timed_region": dict(job.searches)}
+
+    kernels, roofline = {}, None
+    if profile_pass:
+        job.restart()
+        binding.profile_reset()
+        binding.profile_enable(True)
+        touched_sum, pairs_sum = 0, 0
+        for _ in range(K):
+            b = job.step()
+            torch.cuda.synchronize()
+            touched_sum += int(job.out["n_touched"].item())
+            pairs_sum += job.valid_pairs[b]
+        binding.profile_enable(False)
+        prof = binding.profile_collect()
+        mines = job.searches["cold"] + job.searches["warm"]
+        row = wl.d * (2 if wl.dtype == "bf16" else 4)
+        for kname, (ms, cnt) in prof.items():
+            if cnt:
+                kernels[kname] = {"avg_us": ms * 1e3 / cnt, "launches": cnt, "total_ms": ms}
+        traffic, source = _traffic(args.traffic_json, wl.name + ("_structured" if structured else ""))
+        models = {}
+        if "mine_tile" in kernels and mines:
+            # one search sweeps the labels in several launches of the tile kernel; work and time are per search
+            k = kernels["mine_tile"]
+            ms_call = k["total_ms"] / mines
+            t = traffic.get("mine_tile", {})
+            models["mine_tile"] = {"bound": "mfma", "achieved": 2.0 * wl.d * pool * wl.L / (ms_call * 1e-3) / 1e12,
+                                   "peak": PEAK_MFMA_TFLOPS[wl.dtype], "unit": "TFLOP/s", "per": "search",
+                                   "ms": ms_call, "launches_per_search": k["launches"] / mines,
+                                   "searches": dict(job.searches),
+                                   "traffic": t.get("bytes_per_search"),
+                                   "traffic_search_mode": t.get("search_mode"),
+                                   "compulsory_bytes": (wl.L + pool) * row + pool * wl.k_h * 8}
+        if "gather" in kernels:
+            by = pairs_sum / K * row
+            k = kernels["gather"]
+            models["gather"] = {"bound": "hbm", "achieved": by / (k["avg_us"] * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
+                                "unit": "GB/s", "per": "launch", "ms": k["avg_us"] * 1e-3,
+                                "traffic": traffic.get("gather", {}).get("bytes"), "algorithmic_bytes": by}
+        if "update" in kernels:
+            by = 2.0 * touched_sum / K * row
+            k = kernels["update"]
+            models["update"] = {"bound": "hbm", "achieved": by / (k["avg_us"] * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
+                                "unit": "GB/s", "per": "launch", "ms": k["avg_us"] * 1e-3,
+                                "traffic": traffic.get("update", {}).get("bytes"), "algorithmic_bytes": by}
+        for kname, m in models.items():
+            m["frac"] = m["achieved"] / m["peak"]
+            m["kernel"] = kname
+            m["traffic_source"] = source if m["traffic"] is not None else None
+        if models:
+            dominant = max(models, key=lambda n: kernels[n]["total_ms"])
+            roofline = dict(models[dominant])
+            roofline["others"] = {n: m for n, m in models.items() if n != dominant}
+        if "mine_tile" in kernels and mines:
+            per_call_ms = (kernels["mine_tile"]["total_ms"] + kernels.get("mine_select", {"total_ms": 0})["total_ms"]) / mines
+            res["mine_pairs_per_s"] = pool * wl.L / (per_call_ms * 1e-3)
+            res["mine_ms_per_search"] = per_call_ms
+    res["roofline"] = roofline
+    res["kernels_us"] = {n: round(k["avg_us"], 2) for n, k in kernels.items()}
+    del job
+    torch.cuda.empty_cache()
+    return wl, pool, res
 
 
 def main():
@@ -153,37 +313,13 @@ def main():
     import torch
 
     import paper_2409_20156_amd as xc
-    from paper_2409_20156_amd import binding, synth
+    from paper_2409_20156_amd import binding
     if not torch.cuda.is_available():
         raise RuntimeError("bench.py needs a GPU")
     xc.load_library()
-    wl = synth.WORKLOADS[args.workload]
-    pool = args.pool or wl.pool
-    job = Job(wl, pool, warm_margin=args.warm_margin if args.warm_margin >= 0 else None)
-    torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
-        job.step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        job.step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    value = wl.B * args.steps / elapsed
-    # for comparison, the same number of steps with a full search at every refresh (untimed for `value`)
-    full_search = None
-    if job.warm_margin is not None and wl.refresh and not args.no_profile_pass:
-        job.warm_margin = None
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            job.step()
-        torch.cuda.synchronize()
-        el1 = time.perf_counter() - t1
-        full_search = {"value": wl.B * args.steps / el1, "ms_per_step": el1 * 1e3 / args.steps}
-        job.warm_margin = args.warm_margin
-
+    wl, pool, head = run_workload(args, args.workload, steps=args.steps, structured=args.structured,
+                                  profile_pass=not args.no_profile_pass)
     if args.copy_probe_mib:
         a = torch.randint(0, 255, (args.copy_probe_mib << 20,), dtype=torch.uint8, device="cuda:0")
         b = torch.empty_like(a)
@@ -192,82 +328,41 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    # ---- second pass: the same number of steps with per-kernel HIP events --------------
-    roofline, kernels, mines = None, {}, 0
-    if not args.no_profile_pass:
-        binding.profile_reset()
-        binding.profile_enable(True)
-        touched_sum, pairs_sum = 0, 0
-        for _ in range(args.steps):
-            if (wl.refresh and job.t % wl.refresh == 0) or (not wl.refresh and job.t == 0):
-                mines += 1
-            b = job.step()
-            torch.cuda.synchronize()
-            touched_sum += int(job.out["n_touched"].item())
-            pairs_sum += job.valid_pairs[b]
-        if mines == 0:
-            # the schedule mined before the timed steps (one pass over the pool): one more pass here,
-            # outside the timed region, so that the mining kernel of this workload is reported too
-            job.mine()
-            torch.cuda.synchronize()
-            mines = 1
-        binding.profile_enable(False)
-        prof = binding.profile_collect()
-        e = 2 if wl.dtype == "bf16" else 4
-        row = wl.d * e
-        for name, (ms, cnt) in prof.items():
-            if cnt:
-                kernels[name] = {"avg_us": ms * 1e3 / cnt, "launches": cnt, "total_ms": ms}
-        models = {}
-        if "mine_tile" in kernels:
-            # one mining call sweeps the labels in several launches of the tile kernel (phases);
-            # work and time are summed over the launches of the pass, i.e. a launch-time-weighted rate
-            flops = 2.0 * wl.d * pool * wl.L * mines
-            k = kernels["mine_tile"]
-            models["mine_tile"] = {"bound": "mfma", "achieved": flops / (k["total_ms"] * 1e-3) / 1e12,
-                                   "peak": PEAK_MFMA_TFLOPS[wl.dtype], "unit": "TFLOP/s",
-                                   "launches_per_call": k["launches"] / max(mines, 1)}
-        if "gather" in kernels:
-            by = pairs_sum / args.steps * row
-            k = kernels["gather"]
-            models["gather"] = {"bound": "hbm", "achieved": by / (k["avg_us"] * 1e-6) / 1e9,
-                                "peak": PEAK_HBM_GBS, "unit": "GB/s"}
-        if "update" in kernels:
-            by = 2.0 * touched_sum / args.steps * row
-            k = kernels["update"]
-            models["update"] = {"bound": "hbm", "achieved": by / (k["avg_us"] * 1e-6) / 1e9,
-                                "peak": PEAK_HBM_GBS, "unit": "GB/s"}
-        traffic = {}
-        if os.path.exists(args.traffic_json):
-            try:
-                traffic = json.load(open(args.traffic_json)).get(wl.name, {})
-            except Exception:
-                traffic = {}
-        for name, m in models.items():
-            m["frac"] = m["achieved"] / m["peak"]
-            t = traffic.get(name)
-            m["traffic"] = t["bytes"] if t else None       # HBM bytes per launch (read + written)
-            m["kernel"] = name
-            m["avg_us"] = kernels[name]["avg_us"]
-        if models:
-            dominant = max(models, key=lambda n: kernels[n]["total_ms"])
-            roofline = dict(models[dominant])
-            roofline["others"] = {n: m for n, m in models.items() if n != dominant}
-
     result = {
         "metric": "queries/s through xc_step + mining",
-        "value": value, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["value"], "unit": "queries/s", "n_gpus": 1, "steps": head["steps"], "warmup": head["warmup"],
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": "%s: L=%d d=%d %s B=%d k_p<=%d k_h=%d k_r=%d pool=%d refresh=%d"
-                               % (wl.name, wl.L, wl.d, wl.dtype, wl.B, wl.k_p, wl.k_h, wl.k_r, pool, wl.refresh),
-                   "loss": "bce",
-                   "refresh_search": ("exact, warm start from the previous thresholds (margin %g)" % args.warm_margin)
-                                     if args.warm_margin >= 0 else "exact, full search every time"},
-        "roofline": roofline,
-        "full_search_every_refresh": full_search,
-        "kernels_us": {n: round(k["avg_us"], 2) for n, k in kernels.items()},
+        "config": {"workload": head["workload"], "loss": "bce",
+                   "searches_in_timed_region": head["searches_in_timed_region"],
+                   "search": "exact; the first of a scripted run from scratch" +
+                             (", later ones from the previous thresholds (margin %g)" % args.warm_margin
+                              if args.warm_margin >= 0 else ", every one from scratch")},
+        "roofline": head["roofline"],
+        "kernels_us": head["kernels_us"],
     }
+    for k in ("mine_pairs_per_s", "mine_ms_per_search"):
+        if k in head:
+            result[k] = head[k]
+
+    default_run = args.workload == HEADLINE and not args.steps and not args.pool and not args.structured
+    if default_run and not args.no_structured_line and not args.no_profile_pass:
+        # the structured variant of the same workload (queries pulled towards a positive), beside the i.i.d. run
+        _, _, st = run_workload(args, args.workload, structured=True, profile_pass=True)
+        result["structured"] = {k: st[k] for k in ("workload", "value", "ms_per_step", "mine_ms_per_search") if k in st}
+        if st.get("roofline"):
+            result["structured"]["mine_frac"] = (st["roofline"] if st["roofline"]["kernel"] == "mine_tile"
+                                                 else st["roofline"]["others"].get("mine_tile", {})).get("frac")
+    also = args.also
+    if also is None:
+        also = "c2,c3,c4" if default_run and not args.no_profile_pass else "none"
+    others = {}
+    for name in [n for n in also.split(",") if n and n != "none"]:
+        _, _, r = run_workload(args, name, profile_pass=not args.no_profile_pass)
+        others[name] = r
+    if others:
+        result["other_workloads"] = others
+
     # ---- what the chip sustains on two trivial kernels (context for the fractions above) -----
     achievable = {}
     if not args.no_profile_pass:
@@ -291,12 +386,8 @@ def main():
         del a, b
     result["achievable"] = achievable
 
-    if "mine_tile" in kernels:
-        per_call_ms = (kernels["mine_tile"]["total_ms"] + kernels.get("mine_select", {"total_ms": 0})["total_ms"]) / max(mines, 1)
-        result["mine_pairs_per_s"] = pool * wl.L / (per_call_ms * 1e-3)
-        result["mine_ms_per_refresh"] = per_call_ms
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, pool)
+        result["cpu_baseline"] = cpu_baseline(wl, pool, head["steps"])
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result))

@@ -34,10 +34,11 @@ typedef enum { XC_LOSS_BCE = 0, XC_LOSS_SOFTMAX = 1 } xc_loss;
 
 typedef enum {
     XC_OK = 0,
-    XC_EINVAL = -1,      /* null or misaligned pointer, bad enum value            */
+    XC_EINVAL = -1,      /* null or misaligned pointer, bad loss kind or margin   */
     XC_ESHAPE = -2,      /* unsupported or inconsistent sizes                     */
     XC_EWORKSPACE = -3,  /* workspace smaller than xc_*_workspace reports         */
-    XC_EHIP = -4         /* a HIP runtime call failed; see xc_last_hip_error()    */
+    XC_EHIP = -4,        /* a HIP runtime call failed; see xc_last_hip_error()    */
+    XC_EDTYPE = -5       /* element type that is neither XC_F32 nor XC_BF16       */
 } xc_status;
 
 /* limits checked by the host side of every call */

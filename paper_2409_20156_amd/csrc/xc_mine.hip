@@ -795,7 +795,7 @@ static int64_t phase_tiles(int64_t lo, int64_t nQT) {
 }
 
 static int plan_mine(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, MinePlan* p) {
-    if (t != XC_F32 && t != XC_BF16) return XC_EINVAL;
+    if (t != XC_F32 && t != XC_BF16) return XC_EDTYPE;
     if (Zq < 1 || L < 1 || d < 1 || k_h < 1 || k_h > XC_MAX_K_MINE || k_h > L) return XC_ESHAPE;
     const int64_t row_bytes = static_cast<int64_t>(d) * (t == XC_F32 ? 4 : 2);
     if (row_bytes % 16 != 0 || row_bytes > (1 << 20)) return XC_ESHAPE;

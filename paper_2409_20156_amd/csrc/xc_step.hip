@@ -755,9 +755,13 @@ void heads_write_kernel(const uint2* __restrict__ pairs, int64_t P, int64_t chun
 // more than kLongSeg pairs (a frequent positive, a hard negative of many queries) would make
 // its group the last to finish: such segments are queued and afterwards worked on by the whole
 // workgroup, group g taking pairs g, g + NG, ... and the partial sums added in group order.
+// Which segments are queued depends on the data alone (every group queues the first
+// kLongPerGroup long segments it meets, in its own fixed order), never on timing, so the order
+// in which a row's terms are added is the same in every run.
 // ---------------------------------------------------------------------------
 constexpr int kLongSeg = 16;        // pairs above which a segment is shared by the workgroup
-constexpr int kMaxLong = 32;        // queued long segments per workgroup (more are done in place)
+constexpr int kLongPerGroup = 8;    // long segments a group may queue (its first ones; later ones are done in place)
+constexpr int kMaxGroups = kStepThreads / 16;      // groups of a workgroup at most (G >= 16)
 
 template <typename T, int CPL, bool STREAM>
 __global__ __launch_bounds__(kStepThreads)
@@ -770,11 +774,10 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
     constexpr int EPC = Elem<T>::kPerChunk;
     constexpr int U = 2;
     extern __shared__ float lpart[];              // [NG][CPL][G][EPC] partial sums of a long segment
-    __shared__ int long_q[kMaxLong];
-    __shared__ int n_long;
+    __shared__ int long_q[kMaxGroups * kLongPerGroup];   // [group][slot]
+    __shared__ int long_n[kMaxGroups];                    // slots filled by each group
     const int tid = threadIdx.x;
-    if (tid == 0) n_long = 0;
-    __syncthreads();
+    int my_long = 0;                                      // uniform within the group
     // dZ = sum of the partials written by the workgroups that shared a query, in split order
     // (independent of the row updates below; done here because this grid is large)
     if (SQ > 1) {
@@ -839,14 +842,10 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
     const int64_t s_cur = s;
     if (s + s_step < n_seg) { h_n = h_nn; load_hop2(h_n, wv_n, z0_n, g0_n); }
     if (s + 2 * s_step < n_seg) load_hop1(s + 2 * s_step, h_nn);
-    if (p1 - p0 > kLongSeg) {                     // uniform within the group
-        int slot = 0;
-        if (gl == 0) slot = atomicAdd(&n_long, 1);
-        slot = __shfl(slot, 0, G);
-        if (slot < kMaxLong) {
-            if (gl == 0) long_q[slot] = static_cast<int>(s_cur);
-            continue;
-        }
+    if (p1 - p0 > kLongSeg && my_long < kLongPerGroup) {        // uniform within the group
+        if (gl == 0) long_q[(tid / G) * kLongPerGroup + my_long] = static_cast<int>(s_cur);
+        ++my_long;
+        continue;
     }
     unsigned char* wrow = reinterpret_cast<unsigned char*>(W) + label * row_bytes;
 
@@ -917,12 +916,15 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
     }
     }   // segments of this group
 
-    // ---- queued long segments: the whole workgroup on each
-    __syncthreads();
-    const int nl = n_long < kMaxLong ? n_long : kMaxLong;
+    // ---- queued long segments: the whole workgroup on each, in (group, slot) order
     const int grp = tid / G;
-    for (int li = 0; li < nl; ++li) {
-        const int64_t sl = long_q[li];
+    if (gl == 0) long_n[grp] = my_long;
+    __syncthreads();
+    int li = -1;
+    for (int qg = 0; qg < NG; ++qg)
+    for (int qs = 0; qs < long_n[qg]; ++qs) {
+        ++li;
+        const int64_t sl = long_q[qg * kLongPerGroup + qs];
         const int p0 = seg_start[sl], p1 = seg_start[sl + 1];
         const int64_t label = touched[sl];
         float acc[CPL][EPC];
@@ -1022,7 +1024,7 @@ struct StepPlan {
 };
 
 static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t, StepPlan* p) {
-    if (t != XC_F32 && t != XC_BF16) return XC_EINVAL;
+    if (t != XC_F32 && t != XC_BF16) return XC_EDTYPE;
     if (B < 1 || d < 1 || k_p < 0 || k_p > XC_MAX_KP || n_neg < 0) return XC_ESHAPE;
     const int64_t n = static_cast<int64_t>(k_p) + n_neg;
     if (n < 1 || n > XC_MAX_CANDIDATES) return XC_ESHAPE;
@@ -1181,21 +1183,33 @@ extern "C" int xc_step_workspace(int64_t B, int d, int k_p, int n_neg, xc_dtype 
     return XC_OK;
 }
 
-extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, const int32_t* pos, int k_p,
-                       const int32_t* neg, const float* logq, int n_neg, float lr, xc_loss kind,
-                       xc_dtype t, float* loss, float* dZ, int32_t* touched, int32_t* n_touched,
-                       void* W_rows_out, void* ws, size_t ws_bytes, void* stream) {
-    using namespace xc;
+namespace xc {
+// host-side checks of a step's arguments (everything but the workspace); fills the launch plan
+static int check_step_args(const void* Z, const void* W, int64_t B, int64_t L, int d, const int32_t* pos, int k_p,
+                           const int32_t* neg, const float* logq, int n_neg, xc_loss kind, xc_dtype t,
+                           const float* loss, const float* dZ, const int32_t* touched, const int32_t* n_touched,
+                           const void* W_rows_out, StepPlan* pl) {
     if (kind != XC_LOSS_BCE && kind != XC_LOSS_SOFTMAX) return XC_EINVAL;
     if (L < 1 || L > 0x7ffffffeLL) return XC_ESHAPE;
-    StepPlan pl;
-    const int rc = plan_step(B, L, d, k_p, n_neg, t, &pl);
+    const int rc = plan_step(B, L, d, k_p, n_neg, t, pl);
     if (rc != XC_OK) return rc;
-    if (!Z || !W || !loss || !dZ || !touched || !n_touched || !ws) return XC_EINVAL;
+    if (!Z || !W || !loss || !dZ || !touched || !n_touched) return XC_EINVAL;
     if ((k_p > 0 && !pos) || (n_neg > 0 && (!neg || !logq))) return XC_EINVAL;
-    if (!aligned16(Z) || !aligned16(W) || !aligned16(dZ) || !aligned16(ws)) return XC_EINVAL;
+    if (!aligned16(Z) || !aligned16(W) || !aligned16(dZ)) return XC_EINVAL;
     if (W_rows_out && !aligned16(W_rows_out)) return XC_EINVAL;
     if (Z == static_cast<const void*>(dZ)) return XC_EINVAL;
+    return XC_OK;
+}
+
+static int step_impl(const void* Z, void* W, int64_t B, int64_t L, int d, const int32_t* pos, int k_p,
+                     const int32_t* neg, const float* logq, int n_neg, float lr, xc_loss kind,
+                     xc_dtype t, float* loss, float* dZ, int32_t* touched, int32_t* n_touched,
+                     void* W_rows_out, void* ws, size_t ws_bytes, void* stream) {
+    StepPlan pl;
+    const int rc = check_step_args(Z, W, B, L, d, pos, k_p, neg, logq, n_neg, kind, t, loss, dZ, touched,
+                                   n_touched, W_rows_out, &pl);
+    if (rc != XC_OK) return rc;
+    if (!ws || !aligned16(ws)) return XC_EINVAL;
     {   // layout does not depend on L except for the number of sort passes
         StepPlan ref;
         plan_step(B, 0x7ffffffeLL, d, k_p, n_neg, t, &ref);
@@ -1266,4 +1280,14 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
     else launch_update<float>(pl, st, Z, W, d, kin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
     XC_HIP_CHECK(hipGetLastError());
     return XC_OK;
+}
+
+}  // namespace xc
+
+extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, const int32_t* pos, int k_p,
+                       const int32_t* neg, const float* logq, int n_neg, float lr, xc_loss kind,
+                       xc_dtype t, float* loss, float* dZ, int32_t* touched, int32_t* n_touched,
+                       void* W_rows_out, void* ws, size_t ws_bytes, void* stream) {
+    return xc::step_impl(Z, W, B, L, d, pos, k_p, neg, logq, n_neg, lr, kind, t, loss, dZ, touched, n_touched,
+                         W_rows_out, ws, ws_bytes, stream);
 }

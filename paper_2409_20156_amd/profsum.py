@@ -8,7 +8,9 @@
 `stats` lists the library's kernels from a `--kernel-trace --stats` run.  `pmc` averages
 FETCH_SIZE and WRITE_SIZE (KiB per dispatch) per library kernel, scales each by what the same
 counter read for the plain copy kernel of known size in the same run, and writes bytes per
-launch into the JSON file the benchmark reads.  `sq` turns one run with the shader counters
+launch into the JSON file the benchmark reads; for the search it also writes the bytes of one
+whole search (all tile-kernel launches between two `mine_init` launches) and says whether the
+searches of the run started from scratch or from earlier thresholds.  `sq` turns one run with the shader counters
 SQ_VALU_MFMA_BUSY_CYCLES, SQ_INSTS_VALU_MFMA_MOPS_BF16, SQ_BUSY_CU_CYCLES, SQ_WAVE_CYCLES, SQ_WAIT_ANY
 and GRBM_GUI_ACTIVE into matrix-pipe utilisation, the share of their time waves spend waiting, and
 the shader clock.
@@ -22,7 +24,8 @@ import sys
 from collections import defaultdict
 
 # kernel function name -> name used by the benchmark
-KERNELS = {"mine_tile_kernel": "mine_tile", "mine_select_kernel": "mine_select", "mine_init_kernel": "mine_init",
+KERNELS = {"mine_tile_kernel": "mine_tile", "mine_rows_kernel": "mine_tile", "mine_select_kernel": "mine_select",
+           "mine_init_kernel": "mine_init", "mine_warm_init_kernel": "mine_warm_init",
            "sample_kernel": "sample", "gather_kernel": "gather", "radix_count_kernel": "radix_count",
            "radix_prefix_kernel": "radix_scan", "radix_scatter_kernel": "radix_scatter",
            "bucket_sort_kernel": "bucket_sort",
@@ -129,6 +132,19 @@ def pmc(workload, fetch_csv, write_csv, copy_mib, out, traffic_json, cmd):
             f.write("| %s | %d | %.1f | %.1f | %.3f | %.3f |\n" % (n, nf[n], fetch[n], write.get(n, 0.0), rd / 1e6, wr / 1e6))
             if n != "copy_probe":
                 result[n] = {"read_bytes": rd, "write_bytes": wr, "bytes": rd + wr}
+        if "mine_tile" in fetch and nf.get("mine_init"):
+            # every search launches mine_init once; a search started from earlier thresholds also mine_warm_init
+            searches, warm = nf["mine_init"], nf.get("mine_warm_init", 0)
+            mode = "from scratch" if warm == 0 else ("from earlier thresholds" if warm == searches else
+                                                      "%d from scratch, %d from earlier thresholds" % (searches - warm, warm))
+            per = nf["mine_tile"] / searches
+            r = result["mine_tile"]
+            r.update({"searches": searches, "search_mode": mode, "launches_per_search": per,
+                      "read_bytes_per_search": r["read_bytes"] * per, "write_bytes_per_search": r["write_bytes"] * per,
+                      "bytes_per_search": r["bytes"] * per})
+            f.write("\nThe run held %d search(es), %s: %.1f tile-kernel launches per search, %.3f GB read and %.3f GB "
+                    "written per search.\n" % (searches, mode, per, r["read_bytes_per_search"] / 1e9,
+                                               r["write_bytes_per_search"] / 1e9))
     data = {}
     if os.path.exists(traffic_json):
         data = json.load(open(traffic_json))

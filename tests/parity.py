@@ -18,9 +18,19 @@ def check_topk(ids_gpu, sc_gpu, ids_or, sc_or, Z64, W64, tie_rel=1e-5, score_rto
     """Top-k parity with the tie clause: an id may differ from the oracle's only
     where its exact score is within tie_rel (relative) of the oracle's k-th
     score, resp. of the score at the same rank.  Returns the number of queries
-    that needed the clause."""
+    that needed the clause.  W64 is the float64 matrix, or, where that is too
+    large to hold, a function (ids) -> float64 rows together with the label count."""
     ids_gpu = np.asarray(ids_gpu)
     n_tied = 0
+    if isinstance(W64, tuple):
+        rows_of, n_labels = W64
+
+        class _Rows:
+            shape = (n_labels,)
+
+            def __getitem__(self, idx):
+                return rows_of(np.atleast_1d(np.asarray(idx, dtype=np.int64)))[0 if np.ndim(idx) == 0 else slice(None)]
+        W64 = _Rows()
     for i in range(ids_or.shape[0]):
         if (ids_gpu[i] == ids_or[i]).all():
             continue

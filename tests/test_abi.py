@@ -50,7 +50,7 @@ def test_host_side_argument_checks(lib):
     assert b.xc_mine_workspace(128, 1000, 64, 129, 1, ctypes.byref(n)) == -2      # k_h too large
     assert b.xc_mine_workspace(128, 4, 64, 8, 1, ctypes.byref(n)) == -2           # k_h > L
     assert b.xc_mine_workspace(128, 1000, 60, 8, 1, ctypes.byref(n)) == -2        # row not 16-byte multiple
-    assert b.xc_mine_workspace(128, 1000, 64, 8, 7, ctypes.byref(n)) == -1        # bad dtype
+    assert b.xc_mine_workspace(128, 1000, 64, 8, 7, ctypes.byref(n)) == -5        # bad dtype
     assert b.xc_mine_workspace(128, 1000, 64, 8, 1, None) == -1
     assert b.xc_step_workspace(32, 64, 1, 24, 0, ctypes.byref(n)) == 0 and n.value > 0
     big = n.value

@@ -142,8 +142,8 @@ def test_step_is_bitwise_reproducible():
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 def test_step_many_long_segments(dtype):
     """Every label is shared by 17 pairs (more than a lane group takes alone) and there are enough
-    such labels that some workgroups exceed their queue of shared segments: both the cooperative
-    path and the in-place path of the row update are exercised."""
+    such labels that lane groups exceed their queue of shared segments: both the cooperative
+    path and the in-place path of the row update are exercised, and the result is reproducible."""
     B, L, d, k_p, n = 1088, 90000, 64, 1, 1280            # 64 blocks of 17 queries with the same negatives
     Z = synth.make_matrix(8, synth.TAG_Z, B, d, dtype, "cuda:0")
     W = synth.make_matrix(8, synth.TAG_W, L, d, dtype, "cuda:0")
@@ -151,9 +151,58 @@ def test_step_many_long_segments(dtype):
     neg = (blk[:, None] * n + np.arange(n)[None, :]).astype(np.int32)          # < 64 * 1280 = 81920
     pos = (81920 + np.arange(B) % 5000).astype(np.int32).reshape(B, 1)         # positives elsewhere
     logq = np.full((B, n), np.log(0.5), dtype=np.float32)
-    out, ref = _run_and_check(Z, W, pos, neg, logq, f64(Z), f64(W), 0.05 if dtype == torch.bfloat16 else 0.3,
-                              orc.LOSS_BCE)
+    lr = 0.05 if dtype == torch.bfloat16 else 0.3
+    out, ref = _run_and_check(Z, W, pos, neg, logq, f64(Z), f64(W), lr, orc.LOSS_BCE)
     assert len(ref["touched"]) == 64 * n + B
+    # which long segments a workgroup shares and which a lane group sums alone is a function of the
+    # data, not of timing: three runs give the same bits
+    import paper_2409_20156_amd as xc
+    res = []
+    for _ in range(3):
+        Wg = W.clone()
+        xc.xc_step(Z, Wg, torch.tensor(pos, device="cuda:0"), torch.tensor(neg, device="cuda:0"),
+                   torch.tensor(logq, device="cuda:0"), lr)
+        torch.cuda.synchronize()
+        res.append(Wg.view(torch.int16 if dtype == torch.bfloat16 else torch.int32).cpu())
+    assert torch.equal(res[0], res[1]) and torch.equal(res[0], res[2])
+
+
+def test_step_long_segments_beyond_the_queue_are_reproducible_and_exact():
+    """307 200 labels of 17 pairs each: every lane group of the row update meets more long segments than
+    it may queue for the whole workgroup, so the later ones are summed by the group alone.  Which path a
+    segment takes is a function of its position only; three runs give the same bits, and sampled rows
+    of both kinds match the oracle on the sub-problem of the label's 17 queries."""
+    import paper_2409_20156_amd as xc
+    B, L, d, n, lr = 2176, 320000, 64, 2400, 0.05             # 128 blocks of 17 queries with the same negatives
+    dev = "cuda:0"
+    Z = synth.make_matrix(9, synth.TAG_Z, B, d, torch.bfloat16, dev)
+    W = synth.make_matrix(9, synth.TAG_W, L, d, torch.bfloat16, dev)
+    blk = np.arange(B) // 17
+    neg = (blk[:, None] * n + np.arange(n)[None, :]).astype(np.int32)          # < 128 * 2400 = 307200
+    pos = (310000 + np.arange(B) % 5000).astype(np.int32).reshape(B, 1)
+    logq = np.full((B, n), np.log(0.5), dtype=np.float32)
+    tp, tn, tl = (torch.tensor(a, device=dev) for a in (pos, neg, logq))
+    res = []
+    for _ in range(3):
+        Wg = W.clone()
+        out = xc.xc_step(Z, Wg, tp, tn, tl, lr)
+        torch.cuda.synchronize()
+        res.append(Wg)
+    assert int(out["n_touched"].item()) == 128 * n + B
+    assert torch.equal(res[0].view(torch.int16), res[1].view(torch.int16))
+    assert torch.equal(res[0].view(torch.int16), res[2].view(torch.int16))
+    rng = np.random.default_rng(9)
+    labels = np.concatenate([rng.integers(0, 200000, size=12), rng.integers(270000, 307200, size=12)])
+    Z64 = f64(Z)
+    for l in labels:
+        qsel = np.where(blk == l // n)[0]
+        rows = f64(W[int(l):int(l) + 1])
+        ref = orc.xc_step(Z64[qsel], rows, np.full((len(qsel), 1), -1, np.int32),
+                          np.zeros((len(qsel), 1), np.int32), logq[qsel, :1], lr * len(qsel) / B, storage="bf16")
+        gsum = sum(abs(g) for c in ref["coef"] for _, g in c)
+        slack = 2e-6 * lr * len(qsel) / B * gsum * np.abs(Z64[qsel]).max()
+        check_bf16_rows(f64(res[0][int(l):int(l) + 1]), ref["W_rows"], rows, "row %d" % l,
+                        max_mismatch_frac=3.0 / d, slack=[slack])   # one row of 64 elements: at most three one ulp off
 
 
 @pytest.mark.parametrize("B,L,d,k_p,n_neg,masked", [
