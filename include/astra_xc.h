@@ -38,7 +38,9 @@ typedef enum {
     XC_ESHAPE = -2,      /* unsupported or inconsistent sizes                     */
     XC_EWORKSPACE = -3,  /* workspace smaller than xc_*_workspace reports         */
     XC_EHIP = -4,        /* a HIP runtime call failed; see xc_last_hip_error()    */
-    XC_EDTYPE = -5       /* element type that is neither XC_F32 nor XC_BF16       */
+    XC_EDTYPE = -5,      /* element type that is neither XC_F32 nor XC_BF16       */
+    XC_ESCRATCH = -6     /* xc_step_static: the step's temporaries exceed
+                            XC_STATIC_SCRATCH_BYTES                               */
 } xc_status;
 
 /* limits checked by the host side of every call */
@@ -47,6 +49,7 @@ typedef enum {
 #define XC_MAX_ROW_BYTES 4096  /* d * sizeof(element) accepted by xc_step          */
 #define XC_MAX_CANDIDATES 16384 /* k_p + n_neg accepted by xc_step                 */
 #define XC_MAX_KP 256          /* k_p accepted by xc_step                          */
+#define XC_STATIC_SCRATCH_BYTES (32u << 20)  /* temporaries xc_step_static can hold    */
 
 const char* xc_strerror(int status);
 int xc_last_hip_error(void);
@@ -162,6 +165,28 @@ int xc_step(const void* Z /* [B*d] */, void* W /* [L*d], updated in place */, in
             float* dZ /* [B*d] out */, int32_t* touched /* [B*(k_p+n_neg)] out */,
             int32_t* n_touched /* [1] out */, void* W_rows_out /* [B*(k_p+n_neg)*d] or NULL */,
             void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * xc_step for callers that cannot allocate device memory and have no workspace to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error behaviour as xc_step, without `ws`/`ws_bytes`: the step's
+ * temporaries (sort pairs, coefficients, histograms, segment starts, partial sums) live in an
+ * array of XC_STATIC_SCRATCH_BYTES that is part of the library's device image, one per GPU, held
+ * until the process ends.  The call allocates and frees nothing; its first call on a device asks
+ * the runtime once for the array's address there.  A shape for which xc_step_workspace reports
+ * more than XC_STATIC_SCRATCH_BYTES is refused with XC_ESCRATCH before anything is launched
+ * (the c2 and c3 benchmark shapes fit, c4 and c5 do not).  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU (two streams, two threads) race and give
+ * wrong results; calls on one stream, or ordered by events, are safe.  Nothing needs clearing
+ * between calls: every temporary is written before it is read.
+ * ------------------------------------------------------------------------- */
+int xc_step_static(const void* Z /* [B*d] */, void* W /* [L*d], updated in place */, int64_t B,
+                   int64_t L, int d, const int32_t* pos /* [B*k_p] */, int k_p,
+                   const int32_t* neg /* [B*n_neg] */, const float* logq /* [B*n_neg] */, int n_neg,
+                   float lr, xc_loss kind, xc_dtype t, float* loss /* [1] out */,
+                   float* dZ /* [B*d] out */, int32_t* touched /* [B*(k_p+n_neg)] out */,
+                   int32_t* n_touched /* [1] out */, void* W_rows_out /* [B*(k_p+n_neg)*d] or NULL */,
+                   void* stream);
 
 /* ---------------------------------------------------------------------------
  * Measurement aid (no passage of the paper: used by the benchmark to time each

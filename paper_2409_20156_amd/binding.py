@@ -42,7 +42,10 @@ _SIGNATURES = {
     "xc_mfma_probe": (_i32, [ctypes.c_void_p, _i32, _i32, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]),
     "xc_step": (_i32, [_ptr, _ptr, _i64, _i64, _i32, _ptr, _i32, _ptr, _ptr, _i32, _f32, _i32, _i32,
                        _ptr, _ptr, _ptr, _ptr, _ptr, _ptr, ctypes.c_size_t, _ptr]),
+    "xc_step_static": (_i32, [_ptr, _ptr, _i64, _i64, _i32, _ptr, _i32, _ptr, _ptr, _i32, _f32, _i32, _i32,
+                              _ptr, _ptr, _ptr, _ptr, _ptr, _ptr]),
 }
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class XcError(RuntimeError):
@@ -194,6 +197,33 @@ def step_workspace(B: int, d: int, k_p: int, n_neg: int, dtype_code: int) -> int
     n = ctypes.c_size_t(0)
     _check(lib.xc_step_workspace(B, d, k_p, n_neg, dtype_code, ctypes.byref(n)), "xc_step_workspace")
     return n.value
+
+
+def xc_step_static(Z: torch.Tensor, W: torch.Tensor, pos: torch.Tensor, neg: torch.Tensor, logq: torch.Tensor,
+                   lr: float, *, kind: int = XC_LOSS_BCE, out: dict) -> dict:
+    """xc_step through the entry point that allocates nothing: temporaries live in the library's static
+    device array, every output tensor comes from the caller in `out` (loss, dZ, touched, n_touched and
+    optionally W_rows).  Raises XcError(-6) when the shape needs more than STATIC_SCRATCH_BYTES."""
+    lib = load_library()
+    code = _dtype_code(Z)
+    if W.dtype != Z.dtype or Z.shape[1] != W.shape[1]:
+        raise ValueError("Z [B,d] and W [L,d] must share dtype and d")
+    B, d = Z.shape
+    L = W.shape[0]
+    k_p, n_neg = pos.shape[1], neg.shape[1]
+    if pos.shape[0] != B or neg.shape[0] != B or tuple(logq.shape) != tuple(neg.shape):
+        raise ValueError("pos [B,k_p], neg [B,n_neg], logq [B,n_neg] expected")
+    rows = out.get("W_rows")
+    _check(lib.xc_step_static(_dev(Z, name="Z"), _dev(W, name="W"), B, L, d,
+                              _dev(pos, torch.int32, "pos") if k_p else None, k_p,
+                              _dev(neg, torch.int32, "neg") if n_neg else None,
+                              _dev(logq, torch.float32, "logq") if n_neg else None, n_neg,
+                              float(lr), kind, code, _dev(out["loss"], torch.float32, "loss"),
+                              _dev(out["dZ"], torch.float32, "dZ"), _dev(out["touched"], torch.int32, "touched"),
+                              _dev(out["n_touched"], torch.int32, "n_touched"),
+                              _dev(rows, W.dtype, "W_rows") if rows is not None else None, _stream()),
+           "xc_step_static")
+    return out
 
 
 def xc_step(Z: torch.Tensor, W: torch.Tensor, pos: torch.Tensor, neg: torch.Tensor, logq: torch.Tensor,

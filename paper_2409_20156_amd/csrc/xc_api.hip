@@ -130,6 +130,7 @@ extern "C" const char* xc_strerror(int status) {
         case XC_EWORKSPACE: return "workspace too small";
         case XC_EHIP: return "HIP runtime error (see xc_last_hip_error)";
         case XC_EDTYPE: return "unsupported element type (XC_F32 or XC_BF16 expected)";
+        case XC_ESCRATCH: return "the step's temporaries exceed the static scratch array (XC_STATIC_SCRATCH_BYTES)";
         default: return "unknown status";
     }
 }

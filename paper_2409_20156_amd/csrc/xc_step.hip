@@ -6,6 +6,8 @@
 //   radix sort      (label, pair index) by label, stable, digits of up to 11 bits
 //   heads + update  segment heads -> touched list; per touched label the summed
 //                   gradient over its pairs and the fused SGD row update
+#include <mutex>
+
 #include "xc_common.h"
 
 namespace xc {
@@ -1282,6 +1284,30 @@ static int step_impl(const void* Z, void* W, int64_t B, int64_t L, int d, const 
     return XC_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Scratch memory of the entry point that allocates nothing: one array per GPU, part of the
+// library's device image, held until the process ends.  In host code the array's name is only a
+// handle; its device address is asked for once per device and kept.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[XC_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mu;
+static void* scratch_ptr[kMaxDevices];      // device address of `scratch` on each GPU, null = not asked yet
+
+static int static_scratch(void** out) {
+    int dev = 0;
+    XC_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return XC_ESHAPE;
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        XC_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr) return XC_EHIP;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return XC_OK;
+}
 }  // namespace xc
 
 extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, const int32_t* pos, int k_p,
@@ -1290,4 +1316,29 @@ extern "C" int xc_step(const void* Z, void* W, int64_t B, int64_t L, int d, cons
                        void* W_rows_out, void* ws, size_t ws_bytes, void* stream) {
     return xc::step_impl(Z, W, B, L, d, pos, k_p, neg, logq, n_neg, lr, kind, t, loss, dZ, touched, n_touched,
                          W_rows_out, ws, ws_bytes, stream);
+}
+
+extern "C" int xc_step_static(const void* Z, void* W, int64_t B, int64_t L, int d, const int32_t* pos, int k_p,
+                              const int32_t* neg, const float* logq, int n_neg, float lr, xc_loss kind,
+                              xc_dtype t, float* loss, float* dZ, int32_t* touched, int32_t* n_touched,
+                              void* W_rows_out, void* stream) {
+    // host-side checks first, the device is not touched before they pass: sizes (a shape whose temporaries do
+    // not fit the array is refused), then pointers
+    size_t need = 0;
+    const int rc = xc_step_workspace(B, d, k_p, n_neg, t, &need);
+    if (rc != XC_OK) return rc;
+    if (need > static_cast<size_t>(XC_STATIC_SCRATCH_BYTES)) return XC_ESCRATCH;
+    {
+        xc::StepPlan pl;
+        const int rp = xc::check_step_args(Z, W, B, L, d, pos, k_p, neg, logq, n_neg, kind, t, loss, dZ, touched,
+                                           n_touched, W_rows_out, &pl);
+        if (rp != XC_OK) return rp;
+    }
+    void* ws = nullptr;
+    const int rs = xc::static_scratch(&ws);
+    if (rs != XC_OK) return rs;
+    // every temporary of the step is written before it is read, so what an earlier call left in the
+    // array does not matter and nothing has to be cleared
+    return xc::step_impl(Z, W, B, L, d, pos, k_p, neg, logq, n_neg, lr, kind, t, loss, dZ, touched, n_touched,
+                         W_rows_out, ws, static_cast<size_t>(XC_STATIC_SCRATCH_BYTES), stream);
 }

@@ -70,5 +70,13 @@ def test_host_side_argument_checks(lib):
     assert b.xc_mine_negatives_warm(None, None, 1, 100, 64, 200, 1, 0.1, None, None, None, 0, None) == -2   # k_h > L
     assert b.xc_step(None, None, 32, 4096, 64, None, 1, None, None, 24, 0.1, 0, 0, None, None, None,
                      None, None, None, big, None) == -1
+    # the entry point without a workspace: same checks, and shapes beyond its static array are refused
+    assert b.xc_step_static(None, None, 32, 4096, 64, None, 1, None, None, 24, 0.1, 0, 0, None, None, None,
+                            None, None, None) == -1
+    assert b.xc_step_static(None, None, 32, 4096, 64, None, 1, None, None, 24, 0.1, 0, 7, None, None, None,
+                            None, None, None) == -5
+    assert b.xc_step_static(None, None, 2048, 1300000, 768, None, 8, None, None, 1124, 0.1, 0, 1, None, None,
+                            None, None, None, None) == -6
+    assert b.xc_strerror(-6).decode().startswith("the step's temporaries")
     assert b.xc_strerror(-2).decode().startswith("unsupported")
     assert b.xc_version() >= 1
