@@ -24,6 +24,7 @@
 //   mine_select_kernel  after each phase, one wave per query cuts the global
 //       candidate list to its best k and publishes the new tau; after the last
 //       phase it sorts the winners by (score descending, id ascending).
+#include <cstdlib>
 #include <mutex>
 #include <type_traits>
 
@@ -612,6 +613,344 @@ void mine_tile_kernel(const MineArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// The same work item (256 queries x one label slice) for bf16 rows of at most 512 bytes
+// (NK = row bytes / 128 = 1..4), where a wave's share of the query tile fits its registers.
+//   * The query tile never passes through LDS: wave (wm, wn) keeps the MFMA B operands of its 64
+//     queries for the whole row in registers (NK * 32 of them), loaded once per work item.
+//   * Only W is streamed: a label tile is 128 labels, staged 128 bytes of each row at a time
+//     (16 KiB) through a ring of kRing stages in LDS, filled kRing - 1 stages ahead by direct
+//     global->LDS loads, issued by one wave per SIMD in turn.  Half the staged bytes per
+//     flop of the general kernel, and 2 operand reads from LDS per 4 MFMAs instead of 6 per 8.
+//   * A wave computes 64 labels x 64 queries (2 x 2 MFMA blocks).  A lane owns two query columns
+//     and the thresholds of exactly those, which it keeps in registers.  A passing score goes
+//     straight to a candidate list that belongs to the lane alone (4 owners per query: 2 waves
+//     x 2 lane halves, 256 keys each, in the workgroup's part of the workspace), at a position
+//     the lane counts itself: no atomics, no LDS, no barrier on the path.
+//   * A lane's list that could overflow in the next tile is cut to its best k by the lane's wave
+//     (every label of the overall best k that is in this list is among the list's own best k),
+//     and the lane's threshold rises to the k-th of them.  Nothing of that involves other waves.
+//   * At the end of the slice the four lists of a query are appended to its global list, cut to
+//     the best k first if they hold more than a slice may append.
+// ---------------------------------------------------------------------------
+constexpr int kRowTile = 128;       // labels per tile of the row kernel
+constexpr int kRing = 8;            // stages of 16 KiB in LDS
+constexpr int kRowStage = kRowTile * kStageBytes;
+static_assert(kRing >= 4 && (kRing & (kRing - 1)) == 0, "stage slots are indexed modulo a power of two, and the two halves of the workgroup fill them in turn");
+constexpr int kSubCap = kCandCap / 4;            // keys of a lane's own list
+constexpr int kSubFull = kSubCap - 32;           // above this a tile could overflow it (a lane adds <= 32 per column)
+constexpr size_t kRowsLds = static_cast<size_t>(kRing) * kRowStage + kBN * 4 * sizeof(int) + kMineWaves * 256 * sizeof(int);
+
+// XC_MINE_GENERAL=1 in the environment sends every shape through the general tile kernel (for A/B timing)
+static bool force_general_kernel() {
+    static const bool v = [] { const char* e = getenv("XC_MINE_GENERAL"); return e != nullptr && e[0] == '1'; }();
+    return v;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmem_at_most() {   // until at most N vector memory operations are outstanding
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | 0x0070 | 0x0f00);
+}
+
+// Stage fill of the last, ragged label tile: per-lane addresses, rows past the end repeat the last row.
+__device__ __noinline__ void issue_stage_ragged(const unsigned char* W, int64_t L, int64_t row, int row_bytes, int kbyte,
+                                                uint32_t dcol0, uint32_t dcol1, uint32_t dst) {
+#pragma unroll 1
+    for (int t = 0; t < 4; ++t) {
+        int64_t r = row + 8 * t;
+        r = r < L ? r : L - 1;
+        lds_dma16(W + r * row_bytes + kbyte + ((t & 1) ? dcol1 : dcol0), __builtin_amdgcn_readfirstlane(dst + t * 1024));
+    }
+}
+
+template <int NK>
+__global__ __launch_bounds__(kMineThreads, 1)
+void mine_rows_kernel(const MineArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    if (a.cond != nullptr && a.cond[0] == 0) return;          // uniform: a repeat that is not needed
+    int* cnt4 = reinterpret_cast<int*>(smem + kRing * kRowStage);            // [kBN][4] list fills at the end of a slice
+    int* hist = cnt4 + kBN * 4;                                             // [kMineWaves][256]
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) unsigned char*)smem));
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1;          // which 64-label half of the tile
+    const int wn = wave >> 1;         // which 64-query quarter
+    const int half = lane >> 5;
+    uint64_t* my_lists = a.lists + static_cast<size_t>(blockIdx.x) * kBN * kCandCap;
+    constexpr int row_bytes = NK * kStageBytes;
+
+    int item, item_step, item_end;
+    int slice_fixed = -1;
+    if (a.Qx > 0) {                   // slices bound to XCDs: workgroup w runs on XCD w % 8
+        const int xcd = blockIdx.x % kXcds;
+        const int cu = blockIdx.x / kXcds;
+        slice_fixed = xcd + kXcds * (cu / a.Qx);
+        item = cu % a.Qx; item_step = a.Qx; item_end = static_cast<int>(a.nQT);
+        if (slice_fixed >= a.S) item_end = 0;
+    } else {
+        item = blockIdx.x; item_step = kMineGrid; item_end = static_cast<int>(a.nQT * a.S);
+    }
+
+    // fragment reads of the A operand (as in the general kernel: row pitch 128, chunks swizzled by (row >> 1) & 7)
+    const int swz = (lane >> 1) & 7;
+    const int frag_a = (wm * 64 + (lane & 31)) * kStageBytes + ((half ^ swz) * 16);
+    // stage fill.  Waves w and w + 4 share a SIMD.  A stage is brought in by four waves, one per SIMD, while
+    // their SIMD-mates start on the MFMAs at once (a wave that issues loads queues at the texture unit behind
+    // the other waves' loads; if all eight issued, every SIMD's matrix pipe would idle meanwhile); waves 0..3
+    // take the even stages, waves 4..7 the odd ones.  Wave w brings in rows 32 (w & 3) .. + 31 of the stage
+    // with four instructions of 8 rows; lane i -> row i / 8, position i % 8, source chunk = position ^ swizzle(row)
+    const int drow = lane >> 3;
+    const int wq = wave & 3;
+    const int my_parity = wave >> 2;
+    const uint32_t dcol[2] = {static_cast<uint32_t>(((lane & 7) ^ (lane >> 4)) * 16),
+                              static_cast<uint32_t>(((lane & 7) ^ ((lane >> 4) + 4)) * 16)};
+    const uint32_t voff[2] = {static_cast<uint32_t>(drow * row_bytes) + dcol[0],
+                              static_cast<uint32_t>((drow + 8) * row_bytes) + dcol[1]};
+    const uint32_t dma_dst = lds_base + wq * 4 * 1024;
+
+    for (; item < item_end; item += item_step) {
+        const int64_t qtile = a.Qx > 0 ? item : item / a.S;
+        if (a.cond != nullptr && a.cond[1 + qtile] == 0) continue;
+        const int slice = a.Qx > 0 ? slice_fixed : static_cast<int>(item % a.S);
+        const int64_t t_begin = a.tile_lo + static_cast<int64_t>(slice) * a.tiles_per_slice;
+        int64_t lab_begin, lab_end;
+        {
+            int64_t t_end = t_begin + a.tiles_per_slice;
+            t_end = t_end < a.tile_hi ? t_end : a.tile_hi;
+            if (t_end <= t_begin) continue;                  // uniform: an empty slice
+            lab_begin = t_begin * kBM;
+            lab_end = t_end * kBM;
+            lab_end = lab_end < a.L ? lab_end : a.L;
+        }
+        const int n_tiles = static_cast<int>((lab_end - lab_begin + kRowTile - 1) / kRowTile);
+        const int n_stages = n_tiles * NK;
+        const int64_t q0 = qtile * kBN;
+
+        // ---- this wave's queries: B operands for the whole row, thresholds of the lane's two columns
+        uint4 zf[NK * 4][2];
+        float tau[2];
+        int cnt[2] = {0, 0};
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const int64_t q = q0 + wn * 64 + nt * 32 + (lane & 31);
+            const int64_t qc = q < a.Zq ? q : a.Zq - 1;
+            tau[nt] = q < a.Zq ? ordered_to_float(a.tau_g[q]) : INFINITY;
+            const unsigned char* zr = a.Z + qc * row_bytes + half * 16;
+#pragma unroll
+            for (int ks = 0; ks < NK * 4; ++ks) zf[ks][nt] = *reinterpret_cast<const uint4*>(zr + ks * 32);
+        }
+
+        // every load so far has landed before the first stage load is issued: from here on the only vector memory
+        // operations in flight are the stage loads (and the filter's rare stores), counted by the waits below
+        wait_all_vmem();
+
+        // ---- the load stream: stage g = (tile g / NK, bytes 128 (g % NK) .. of the rows) goes to slot g % kRing
+        int ld_stage = 0, ld_kb = 0, ld_tile = 0;
+        uint32_t ld_dst = dma_dst;
+        const unsigned char* ld_w = a.W + (lab_begin + wq * 32) * row_bytes;        // this wave's rows of the tile being loaded
+        const int full_tiles = static_cast<int>((a.L - lab_begin) / kRowTile < n_tiles ? (a.L - lab_begin) / kRowTile : n_tiles);
+        auto issue_stage = [&]() {
+            if ((ld_stage & 1) != my_parity) {
+                // the other half's turn
+            } else if (ld_tile < full_tiles) {
+                const uint64_t b64 = reinterpret_cast<uint64_t>(ld_w + ld_kb * kStageBytes);
+                const uint64_t sb =
+                    (static_cast<uint64_t>(static_cast<uint32_t>(
+                         __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32)))) << 32) |
+                    static_cast<uint64_t>(static_cast<uint32_t>(
+                        __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64))));
+                const unsigned char* sp = reinterpret_cast<const unsigned char*>(sb);
+                const unsigned char* sp2 = sp + 16 * row_bytes;
+                lds_dma16_sbase<0>(sp, voff[0], ld_dst);
+                lds_dma16_sbase<1024>(sp, voff[1], ld_dst);
+                lds_dma16_sbase<2048>(sp2, voff[0], ld_dst);
+                lds_dma16_sbase<3072>(sp2, voff[1], ld_dst);
+            } else {
+                // the last tile of the label range: rows past the end repeat the last row (dropped by the filter)
+                issue_stage_ragged(a.W, a.L, lab_begin + static_cast<int64_t>(ld_tile) * kRowTile + wq * 32 + drow,
+                                   row_bytes, ld_kb * kStageBytes, dcol[0], dcol[1], ld_dst);
+            }
+            ++ld_stage;
+            ld_dst += kRowStage;
+            if ((ld_stage & (kRing - 1)) == 0) ld_dst = dma_dst;
+            if (++ld_kb == NK) { ld_kb = 0; ++ld_tile; ld_w += kRowTile * row_bytes; }
+        };
+        // This wave's part of stage g (if it has one) is complete once at most 4 * (its stages issued after g)
+        // loads are outstanding: of the kRing - 2 stages issued after g in the steady state half are this
+        // wave's, whichever half g belongs to.  Stores of the filter only make the wait stricter (loads complete
+        // in order among themselves).  Near the end of the work item everything is awaited.
+        auto wait_stage = [&](int g) {
+            if (ld_stage - 1 - g >= kRing - 2) wait_vmem_at_most<4 * ((kRing - 2) / 2)>();
+            else wait_all_vmem();
+        };
+
+        f32x16 acc[2][2];
+        uint4 fa[2][2];
+        auto read_frags = [&](int slot, int kk, int sel) {
+            const unsigned char* buf = smem + slot * kRowStage;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+                fa[sel][mt] = *reinterpret_cast<const uint4*>(buf + ((frag_a ^ (kk * 32)) + mt * 32 * kStageBytes));
+        };
+        // stage g + 1 visible to everyone, stage g's slot free: refill it, and fetch the first operands of stage g + 1
+        auto publish = [&](int g_next) {
+            wait_stage(g_next);
+            lds_barrier();
+            if (ld_stage < n_stages) issue_stage();
+            read_frags(g_next % kRing, 0, 0);
+        };
+
+        __syncthreads();                                     // the ring and cnt4 are free (previous item closed)
+        for (int s = 0; s < kRing - 1 && s < n_stages; ++s) issue_stage();
+        publish(0);
+
+        // ---- threshold filter of one N block (the lane owns query column (lane & 31) of it) of the tile that
+        // starts at label l0
+        auto filter = [&](auto ntc, int64_t l0) {
+            constexpr int nt = decltype(ntc)::value;
+            const float t = tau[nt];
+            float mx = acc[0][nt][0];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[mt][nt][i]);
+            if (__builtin_expect(__ballot(mx >= t) != 0ull, 0)) {
+                const int qloc = wn * 64 + nt * 32 + (lane & 31);
+                uint64_t* mine = my_lists + static_cast<size_t>(qloc * 4 + wm * 2 + half) * kSubCap;
+                const int32_t lrow = static_cast<int32_t>(l0) + wm * 64 + 4 * half;
+                const int32_t lmax = static_cast<int32_t>(a.L);
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float v = acc[mt][nt][i];
+                        const int32_t lab = lrow + mt * 32 + 8 * (i >> 2) + (i & 3);
+                        const bool hit = v >= t && lab < lmax;      // rows past the end repeat the last row
+                        if (__builtin_expect(__ballot(hit) != 0ull, 0)) {
+                            if (hit) { mine[cnt[nt]] = make_key(v + 0.0f /* -0 -> +0 */, lab); ++cnt[nt]; }
+                        }
+                    }
+            }
+        };
+        // ---- a list that the next tile could overflow: cut to its best k, by this wave alone
+        auto cut_lists = [&]() {
+            if (__builtin_expect(__ballot(cnt[0] > kSubFull || cnt[1] > kSubFull) != 0ull, 0)) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");       // this wave's list stores are complete ...
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");       // ... and are what the loads below see
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    uint64_t todo = __ballot(cnt[nt] > kSubFull);
+                    while (todo) {
+                        const int src = __ffsll(static_cast<long long>(todo)) - 1;
+                        todo &= todo - 1;
+                        const int qsel = wn * 64 + nt * 32 + (src & 31);
+                        const int nsel = __shfl(cnt[nt], src, kWave);
+                        uint64_t* lsel = my_lists + static_cast<size_t>(qsel * 4 + wm * 2 + (src >> 5)) * kSubCap;
+                        const float tk = wave_select_k<kSubCap / kWave>(
+                            lsel, [lsel](int idx) { return lsel[idx]; }, nsel, a.k, hist + wave * 256);
+                        if (lane == src) { cnt[nt] = a.k; tau[nt] = fmaxf(tau[nt], tk); }
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            }
+        };
+
+        // ---- main loop.  (Deferring a block's filter into the next tile's first products, so that the vector
+        // ALU works while the matrix pipe does, was measured and gained nothing: the kernel runs at the chip's
+        // power limit, where the clock falls as the matrix pipe fills.)
+        int g = 0;                                           // stage being computed
+        for (int tile = 0; tile < n_tiles; ++tile) {
+            const int64_t l0 = lab_begin + static_cast<int64_t>(tile) * kRowTile;
+#pragma unroll
+            for (int kb = 0; kb < NK; ++kb) {
+                const int slot = g % kRing;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    const int sel = kk & 1;
+                    if (kk < 3) {
+                        read_frags(slot, kk + 1, sel ^ 1);
+                    } else {
+                        // (reads into fa[0], which the products of kk = 2 have left.  Also after the last stage,
+                        // where the operands read are never used: one way through the loop body, so that no wait
+                        // meant for another way in holds up the products below)
+                        publish(g + 1);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt) {
+                            bf16x8 av, bv;
+                            __builtin_memcpy(&av, &fa[sel][mt], 16);
+                            __builtin_memcpy(&bv, &zf[kb * 4 + kk][nt], 16);
+                            if (kb == 0 && kk == 0) {
+                                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                                acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, zero, 0, 0, 0);
+                            } else {
+                                acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[mt][nt], 0, 0, 0);
+                            }
+                        }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                ++g;
+            }
+            filter(IC<0>{}, l0);
+            filter(IC<1>{}, l0);
+            cut_lists();
+        }
+
+        // ---- close the slice: the four lists of a query go to its global list
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) cnt4[(wn * 64 + nt * 32 + (lane & 31)) * 4 + wm * 2 + half] = cnt[nt];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        {
+            const int ql = wave * 32 + (lane & 31);          // lanes l and l + 32 look after query 32 wave + l
+            const bool qok = (q0 + ql) < a.Zq;
+            int c[4];
+            int n = 0;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) { c[s] = qok ? cnt4[ql * 4 + s] : 0; n += c[s]; }
+            uint64_t* qlist = my_lists + static_cast<size_t>(ql) * kCandCap;
+            uint64_t todo = __ballot(lane < 32 && n > a.append_max);
+            while (todo) {                                   // more than a slice may append: the best k of all four
+                const int src = __ffsll(static_cast<long long>(todo)) - 1;
+                todo &= todo - 1;
+                int cs[4];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) cs[s] = __shfl(c[s], src, kWave);
+                uint64_t* lsel = my_lists + static_cast<size_t>(wave * 32 + src) * kCandCap;
+                auto at = [lsel, &cs](int idx) {
+                    int s = 0;
+                    if (idx >= cs[0]) { idx -= cs[0]; s = 1;
+                        if (idx >= cs[1]) { idx -= cs[1]; s = 2;
+                            if (idx >= cs[2]) { idx -= cs[2]; s = 3; } } }
+                    return lsel[s * kSubCap + idx];
+                };
+                wave_select_k<kCandCap / kWave>(lsel, at, cs[0] + cs[1] + cs[2] + cs[3], a.k, hist + wave * 256);
+                if ((lane & 31) == src) { c[0] = a.k; c[1] = 0; c[2] = 0; c[3] = 0; n = a.k; }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            int base = 0;
+            if (lane < 32 && n > 0) base = atomicAdd(&a.gcnt[q0 + ql], n);
+            base = __shfl(base, lane & 31, kWave);
+            uint64_t* out = a.glist + static_cast<size_t>(q0 + ql) * a.glist_cap;
+            int off = base;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                for (int e = half; e < c[s]; e += 2)
+                    if (off + e < a.glist_cap) out[off + e] = qlist[s * kSubCap + e];
+                off += c[s];
+            }
+        }
+    }
+}
+
 __global__ void mine_init_kernel(uint32_t* tau_g, int32_t* gcnt, int64_t n, uint32_t* zeros /* [64] */,
                                  const int32_t* cond) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -794,6 +1133,25 @@ static int64_t phase_tiles(int64_t lo, int64_t nQT) {
     return best;
 }
 
+// Slices per XCD for the kernel that keeps the query tile in registers.  The compute units of an XCD
+// that work on one slice read the same stream of W tiles, a few tiles apart, so all but the first find
+// them in that XCD's L2: the fewer slices per XCD, the fewer times W comes from memory (with 8 slices
+// per XCD the search of 16 384 queries over 120 M rows of 512 bytes ran at the rate the memory system
+// delivered W, with one slice 19 % faster).  The other side: 32 / slices query tiles are in flight per
+// XCD, and compute units without a query tile idle.  Among the counts the phase allows (<= sx_max) take
+// the one that keeps the most compute units busy, and of those the smallest.
+static int rows_slices_per_xcd(int64_t nQT, int sx_max) {
+    int best = sx_max;
+    double best_eff = -1.0;
+    for (int sx = 1; sx <= sx_max; sx <<= 1) {
+        const int qx = kCusPerXcd / sx;
+        const int64_t rounds = (nQT + qx - 1) / qx;
+        const double eff = static_cast<double>(nQT) / static_cast<double>(rounds * qx);
+        if (eff > best_eff + 1e-9) { best_eff = eff; best = sx; }
+    }
+    return best;
+}
+
 static int plan_mine(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, MinePlan* p) {
     if (t != XC_F32 && t != XC_BF16) return XC_EDTYPE;
     if (Zq < 1 || L < 1 || d < 1 || k_h < 1 || k_h > XC_MAX_K_MINE || k_h > L) return XC_ESHAPE;
@@ -884,6 +1242,13 @@ static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, 
             for (const void* fn : fns)
                 XC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  static_cast<int>(p.lds_tile)));
+            const void* rfns[4] = {reinterpret_cast<const void*>(&mine_rows_kernel<1>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<2>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<3>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<4>)};
+            for (const void* fn : rfns)
+                XC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 static_cast<int>(kRowsLds)));
             if (dev >= 0 && dev < 64) attr_done_mask |= 1ull << dev;
         }
     }
@@ -895,11 +1260,14 @@ static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, 
     // one phase: the tile kernel over label tiles [lo, hi), then the select
     auto phase = [&](int64_t lo, int64_t hi, const int32_t* cond, int32_t* short_flag) -> int {
         const int64_t nT = hi - lo;
+        const bool rows_kernel = t == XC_BF16 && a.row_bytes % kStageBytes == 0 && a.row_bytes <= 4 * kStageBytes &&
+                                 !force_general_kernel();
         if (nT >= kXcds) {
             // slices per XCD: as many as the phase supports, so that few query tiles are in
             // flight per XCD and their Z rows stay in that XCD's L2
             int Sx = 8;
             while (Sx > 1 && (nT < static_cast<int64_t>(kXcds) * Sx || kXcds * Sx > slices_cap(p.kcap))) Sx >>= 1;
+            if (rows_kernel) Sx = rows_slices_per_xcd(p.nQT, Sx);
             a.S = kXcds * Sx;
             a.Qx = kCusPerXcd / Sx;
         } else {                                           // a few tiles: one slice per tile, plain order
@@ -912,7 +1280,15 @@ static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, 
         if (a.append_max > kCandCap) a.append_max = kCandCap;
         a.cond = cond;
         const bool ktail = (a.row_bytes % kStageBytes) != 0;
-        if (t == XC_BF16) {
+        if (rows_kernel) {
+            // short bf16 rows: the query tile stays in registers, only W is streamed
+            switch (a.row_bytes / kStageBytes) {
+                case 1: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<1><<<kMineGrid, kMineThreads, kRowsLds, st>>>(a))); break;
+                case 2: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<2><<<kMineGrid, kMineThreads, kRowsLds, st>>>(a))); break;
+                case 3: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<3><<<kMineGrid, kMineThreads, kRowsLds, st>>>(a))); break;
+                default: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<4><<<kMineGrid, kMineThreads, kRowsLds, st>>>(a))); break;
+            }
+        } else if (t == XC_BF16) {
             if (ktail) XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t, true><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));
             else XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t, false><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));
         } else {

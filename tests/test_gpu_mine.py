@@ -46,6 +46,12 @@ def _case(seed, Zq, L, d, dtype, k):
     (600, 30000, 64, torch.bfloat16, 63),
     (78, 30000, 32, torch.float32, 63),
     (78, 16384, 64, torch.bfloat16, 8),
+    # bf16 rows of 128, 256, 384 and 512 bytes take the kernel that keeps the query tile in registers
+    (300, 70000, 256, torch.bfloat16, 50),     # the row shape of the largest configuration
+    (513, 9000, 192, torch.bfloat16, 100),     # three query tiles, the last with one query; ragged last label tile
+    (64, 200, 256, torch.bfloat16, 128),       # maximum k, fewer labels than two tiles
+    (257, 40000, 128, torch.bfloat16, 64),
+    (31, 127, 64, torch.bfloat16, 127),        # a single ragged label tile, k = L
 ])
 def test_mine_matches_oracle(Zq, L, d, dtype, k):
     print("case", Zq, L, d, dtype, k, flush=True)
@@ -58,12 +64,13 @@ def test_mine_long_slices_exercise_list_reduction():
     _case(5, 512, 131072, 64, torch.bfloat16, 64)
 
 
-@pytest.mark.parametrize("L,Zq,k", [(40000, 140, 33), (300000, 260, 128)])
-def test_mine_increasing_scores_worst_case_for_the_threshold(L, Zq, k):
+@pytest.mark.parametrize("L,Zq,k,d", [(40000, 140, 33, 16), (300000, 260, 128, 16), (40000, 140, 33, 64),
+                                      (300000, 260, 128, 256), (150000, 700, 100, 128)])
+def test_mine_increasing_scores_worst_case_for_the_threshold(L, Zq, k, d):
     # score(i, l) grows with l: every label beats the running threshold, in every phase, so every
-    # accumulator is parked, the pools are emptied all the time and the lists are cut after every tile
+    # accumulator is parked and the candidate lists are cut all the time (32-byte rows: the general kernel,
+    # its pools and shared lists; 128..512-byte rows: the lists of the kernel with register-resident queries)
     dev = "cuda:0"
-    d = 16
     base = torch.ones(d, dtype=torch.float32)
     W = (torch.arange(L, dtype=torch.float32)[:, None] / 65536.0 * base[None, :]).to(torch.bfloat16).to(dev)
     Z = torch.ones((Zq, d), dtype=torch.bfloat16, device=dev)
