@@ -69,8 +69,7 @@ def stats(src, out, title, cmd, trace=None):
 
 def _searches(trace):
     """The mine_tile launches of the trace grouped into searches (a run of mining kernels between other
-    kernels of the library).  A search from scratch is four sweeps; a warm one is one sweep and four launches
-    that return at once, and its mean per launch is the figure bench.py reports as the kernel's average."""
+    kernels of the library)."""
     rows = [r for r in csv.DictReader(open(trace)) if short_name(r["Kernel_Name"]) is not None]
     rows.sort(key=lambda r: int(r["Start_Timestamp"]))
     groups, cur = [], []
@@ -88,9 +87,9 @@ def _searches(trace):
     by = defaultdict(list)
     for g in groups:
         by[len(g)].append(g)
-    out = ["\nmine_tile launches grouped by search (one search = the mining kernels between two steps; four launches: a "
-           "search from scratch; five: a search started from the previous thresholds, whose mean per launch is what "
-           "`bench.py` reports as `roofline.avg_us` from its own HIP events):\n\n",
+    out = ["\nmine_tile launches grouped by search (one search = the mining kernels between two steps: one launch per phase "
+           "of a search from scratch; a search started from earlier thresholds has one sweep and then the same launches, "
+           "which return at once). `bench.py` reports the mean total per search from its own HIP events:\n\n",
            "| launches per search | searches | mean total us | mean per launch us | longest launch us |\n|---|---|---|---|---|\n"]
     for k in sorted(by):
         gs = by[k]
