@@ -247,11 +247,13 @@ def run_workload(args, name, steps=0, warmup=None, structured=False, profile_pas
         job.restart()
         binding.profile_reset()
         binding.profile_enable(True)
-        touched_sum, pairs_sum = 0, 0
+        touched_sum, pairs_sum, single_sum = 0, 0, 0
+        stats = job.step_ws[:4].view(torch.int32)      # rows the gather updated itself (labels with one pair)
         for _ in range(K):
             b = job.step()
             torch.cuda.synchronize()
             touched_sum += int(job.out["n_touched"].item())
+            single_sum += int(stats.item())
             pairs_sum += job.valid_pairs[b]
         binding.profile_enable(False)
         prof = binding.profile_collect()
@@ -275,13 +277,13 @@ def run_workload(args, name, steps=0, warmup=None, structured=False, profile_pas
                                    "traffic_search_mode": t.get("search_mode"),
                                    "compulsory_bytes": (wl.L + pool) * row + pool * wl.k_h * 8}
         if "gather" in kernels:
-            by = pairs_sum / K * row
+            by = (pairs_sum + single_sum) / K * row        # every pair's row read, single-pair rows also written
             k = kernels["gather"]
             models["gather"] = {"bound": "hbm", "achieved": by / (k["avg_us"] * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
                                 "unit": "GB/s", "per": "launch", "ms": k["avg_us"] * 1e-3,
                                 "traffic": traffic.get("gather", {}).get("bytes"), "algorithmic_bytes": by}
         if "update" in kernels:
-            by = 2.0 * touched_sum / K * row
+            by = 2.0 * (touched_sum - single_sum) / K * row     # rows of labels with several pairs: read and written
             k = kernels["update"]
             models["update"] = {"bound": "hbm", "achieved": by / (k["avg_us"] * 1e-6) / 1e9, "peak": PEAK_HBM_GBS,
                                 "unit": "GB/s", "per": "launch", "ms": k["avg_us"] * 1e-3,
@@ -298,6 +300,15 @@ def run_workload(args, name, steps=0, warmup=None, structured=False, profile_pas
             per_call_ms = (kernels["mine_tile"]["total_ms"] + kernels.get("mine_select", {"total_ms": 0})["total_ms"]) / mines
             res["mine_pairs_per_s"] = pool * wl.L / (per_call_ms * 1e-3)
             res["mine_ms_per_search"] = per_call_ms
+    if profile_pass:
+        res["rows_per_step"] = {"touched": touched_sum / K, "updated_in_gather": single_sum / K}
+        # the step as a whole against the memory roofline: every pair's row read once, every touched row written once
+        # and, unless its label has a single pair, read once more
+        step_us = sum(k["total_ms"] for n, k in kernels.items() if n not in ("mine_tile", "mine_select")) * 1e3 / K
+        step_bytes = (pairs_sum + 2.0 * touched_sum - single_sum) / K * row
+        res["step_hbm"] = {"algorithmic_bytes": step_bytes, "kernels_us": step_us,
+                           "achieved_GBs": step_bytes / (step_us * 1e-6) / 1e9,
+                           "frac_of_8TBs": step_bytes / (step_us * 1e-6) / 1e9 / PEAK_HBM_GBS}
     res["roofline"] = roofline
     res["kernels_us"] = {n: round(k["avg_us"], 2) for n, k in kernels.items()}
     del job
@@ -341,7 +352,7 @@ def main():
         "roofline": head["roofline"],
         "kernels_us": head["kernels_us"],
     }
-    for k in ("mine_pairs_per_s", "mine_ms_per_search"):
+    for k in ("mine_pairs_per_s", "mine_ms_per_search", "rows_per_step", "step_hbm"):
         if k in head:
             result[k] = head[k]
 

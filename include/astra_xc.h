@@ -152,6 +152,11 @@ int xc_sample_negatives_mixture(const int32_t* shortlist /* [B*M] */, const floa
  *   to nearest even for bf16).
  *   touched[0..n_touched[0]) = those labels, ascending; no other row changes.
  *   W_rows_out, if not NULL, receives the updated rows in that order.
+ *   (How: the pairs are sorted by label first.  For the BCE loss a label with a single
+ *   unmasked pair gets its row updated while that pair's score is computed, w - lr g z
+ *   rounded once; the other labels are summed over their pairs in pair order afterwards.
+ *   After the call the first 32-bit word of the workspace holds the number of rows of
+ *   the first kind, for measurements.)
  * Z and dZ must not alias.  Requires B >= 1, 0 <= k_p <= XC_MAX_KP, n_neg >= 0,
  * 1 <= k_p + n_neg <= XC_MAX_CANDIDATES, B*(k_p+n_neg) < 2^31,
  * d*sizeof(element) a multiple of 16 and <= XC_MAX_ROW_BYTES.

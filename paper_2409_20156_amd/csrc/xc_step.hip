@@ -140,12 +140,17 @@ __device__ __forceinline__ int lane_of_row(int u, int G) {      // lowest lane o
 // ---------------------------------------------------------------------------
 // FULL: every lane's CPL chunks exist (d / kPerChunk == G * CPL), so no load needs a bounds test; a masked
 // pair then reads the query's own row (finite, and weighted zero) instead of branching around the loads.
-template <typename T, int CPL, int KIND, int U, bool FULL, bool STREAM>
+// FUSE (BCE only): the pair sort has run before this kernel and single_slot[pair] says whether the pair's label
+// occurs in no other unmasked pair of the batch (then: its position in the touched list, else -1).  Such a row
+// is read by this pair alone, its gradient is g z_i with both factors at hand, so it is updated here, while it
+// is in registers (w - lr g z, rounded once), and the row update kernel never sees it: one read and one write of
+// the row in the whole step instead of two reads, a read of z_i and a write.
+template <typename T, int CPL, int KIND, int U, bool FULL, bool STREAM, bool FUSE>
 __global__ __launch_bounds__(kStepThreads)
-void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, int d,
+void gather_kernel(const T* __restrict__ Z, T* W, int64_t L, int d,
                    const int32_t* __restrict__ pos, int k_p, const int32_t* __restrict__ neg,
                    const float* __restrict__ logq, int n_neg, int G, int SQ, int64_t B, float inv_B,
-                   uint2* __restrict__ pairs /* (sort key, pair index) */,
+                   const int32_t* __restrict__ single_slot, float lr, T* rows_out,
                    float* __restrict__ gco, float* __restrict__ loss_q, float* __restrict__ dZ) {
     constexpr int EPC = Elem<T>::kPerChunk;       // U = candidate rows in flight per group
     __shared__ float red[kStepThreads / kWave][kMaxRowFloats];
@@ -168,7 +173,7 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
     const int n = k_p + n_neg;
     const int nchunks = d / EPC;
     const int64_t row_bytes = static_cast<int64_t>(d) * sizeof(T);
-    const unsigned char* Wb = reinterpret_cast<const unsigned char*>(W);
+    unsigned char* Wb = reinterpret_cast<unsigned char*>(W);
     const int32_t* pos_i = pos + i * k_p;
     const int32_t* neg_i = neg + i * n_neg;
     const float* lq_i = logq + i * n_neg;
@@ -186,6 +191,11 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
         }
     }
 
+    float zf[FUSE ? CPL : 1][EPC];     // the query row once more, unpacked, for the fused row updates
+    if (FUSE) {
+#pragma unroll
+        for (int j = 0; j < (FUSE ? CPL : 1); ++j) Elem<T>::unpack(zp[j], zf[j]);
+    }
     float dz[CPL][EPC];            // BCE: sum g w.  soft-max: sum e^{t-m} w
     float pz[CPL][EPC];            // soft-max only: sum over positives of w
 #pragma unroll
@@ -205,6 +215,7 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
     // iteration that uses it begins: nothing waits for them where they are issued, behind the row loads.
     int32_t id_nx[U];
     float lq_nx[U];
+    int32_t sl_nx[FUSE ? U : 1];
     auto fetch_ids = [&](int c0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -213,6 +224,11 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
             cn = cn < n_neg ? cn : n_neg - 1;
             id_nx[u] = -1; lq_nx[u] = 0.0f;
             if (n_neg > 0) { id_nx[u] = neg_i[cn]; lq_nx[u] = lq_i[cn]; }      // uniform
+            if (FUSE) {
+                int ca = c0 + u * NG;
+                ca = ca < n ? ca : n - 1;
+                sl_nx[u] = single_slot[p_base + ca];
+            }
         }
     };
     fetch_ids(grp);
@@ -228,10 +244,12 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
         int32_t id[U];
         float lq[U];
         bool ok[U], isp[U];
+        int32_t slot[FUSE ? U : 1];
         uint4 rw[U][CPL];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u * NG;
+            if (FUSE) slot[u] = sl_nx[u];
             isp[u] = c < k_p;
             const int32_t idp = spos[c & (XC_MAX_KP - 1)];           // read whatever c is, used if c < k_p
             id[u] = isp[u] ? idp : (c < n ? id_nx[u] : -1);
@@ -256,7 +274,7 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
                     const int ch = gl + j * G;
                     rw[u][j] = make_uint4(0, 0, 0, 0);
                     if (ok[u] && ch < nchunks)
-                        rw[u][j] = *reinterpret_cast<const uint4*>(Wb + static_cast<int64_t>(id[u]) * row_bytes + ch * 16);
+                        rw[u][j] = load16<STREAM>(Wb + static_cast<int64_t>(id[u]) * row_bytes + ch * 16);
                 }
             }
         }
@@ -331,14 +349,29 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
 #pragma unroll
                         for (int e = 0; e < EPC; ++e) pz[j][e] += wf[j][e];
                 }
+                if (FUSE) {
+                    if (ok[u] && slot[u] >= 0) {           // the only pair of its label: the row is updated here
+                        const float cg = -lr * g;
+                        unsigned char* wrow = Wb + static_cast<int64_t>(id[u]) * row_bytes;
+                        unsigned char* orow = rows_out ? reinterpret_cast<unsigned char*>(rows_out) +
+                                                             static_cast<int64_t>(slot[u]) * row_bytes : nullptr;
+#pragma unroll
+                        for (int j = 0; j < CPL; ++j) {
+                            const int ch = gl + j * G;
+                            if (FULL || ch < nchunks) {
+#pragma unroll
+                                for (int e = 0; e < EPC; ++e) wf[j][e] = fmaf(cg, zf[j][e], wf[j][e]);
+                                const uint4 o = Elem<T>::pack(wf[j]);
+                                store16<STREAM>(wrow + ch * 16, o);
+                                if (orow) store16<STREAM>(orow + ch * 16, o);
+                            }
+                        }
+                    }
+                }
             }
             float park = g;         // soft-max: the logit is parked until the normaliser is known
             if (KIND == XC_LOSS_SOFTMAX) park = lane_read(src << 2, my_t);
-            if (gl == 0 && c < n) {
-                pairs[p_base + c] = make_uint2(ok[u] ? static_cast<uint32_t>(id[u]) : static_cast<uint32_t>(L),
-                                               static_cast<uint32_t>(p_base + c));
-                gco[p_base + c] = park;
-            }
+            if (gl == 0 && c < n) gco[p_base + c] = park;
         }
     }
     // per-lane partial sums of the group (one lane per row adds) -> every lane of the group
@@ -408,10 +441,12 @@ void gather_kernel(const T* __restrict__ Z, const T* __restrict__ W, int64_t L, 
 
     if (KIND == XC_LOSS_SOFTMAX) {
         // pair coefficients now that the normaliser is known
+        // (a masked pair parked -inf: its coefficient comes out 0 and its key is the masked one, so it is never used;
+        // a query without a positive has all its keys masked)
         for (int c = tid; c < n; c += kStepThreads) {
             const int64_t p = p_base + c;
-            if (npos_all == 0) { pairs[p].x = static_cast<uint32_t>(L); gco[p] = 0.0f; }
-            else if (pairs[p].x != static_cast<uint32_t>(L)) {
+            if (npos_all == 0) gco[p] = 0.0f;
+            else {
                 const float t = gco[p];
                 gco[p] = (expf(t - lse) - (c < k_p ? inv_npos : 0.0f)) * inv_B;
             }
@@ -452,18 +487,68 @@ __device__ __forceinline__ V block_sum(V v, V* sh) {
     return t;
 }
 
+// Where the sort keys come from.  Pair p = i * n + c is candidate c of query i: positive c < k_p, else negative
+// c - k_p.  Its key is the label id, or L (the masked key, sorted behind every label and never touched again) if
+// the id is outside [0, L), if it is a negative that is one of the query's positives (the (1 - y_l) factor of
+// the loss), or, for the soft-max, if the query has no valid positive at all.
+struct KeySource {
+    const int32_t* pos;
+    const int32_t* neg;
+    int k_p, n_neg, n, n_shift, softmax;
+    uint32_t n_magic;
+    int64_t L;
+};
+__device__ __forceinline__ uint32_t pair_index_to_query(uint32_t idx, uint32_t n_magic, int n_shift) {
+    // exact division by n through a multiply-high (constants from the host; valid for every index below 2^31)
+    if (n_shift < 0) return idx;                                   // n == 1
+    const uint32_t t = __umulhi(idx, n_magic);
+    return (t + ((idx - t) >> 1)) >> n_shift;
+}
+__device__ __forceinline__ uint32_t pair_key(const KeySource& k, uint32_t p) {
+    const uint32_t i = pair_index_to_query(p, k.n_magic, k.n_shift);
+    const int c = static_cast<int>(p - i * static_cast<uint32_t>(k.n));
+    const int32_t* pos_i = k.pos + static_cast<int64_t>(i) * k.k_p;
+    const bool isp = c < k.k_p;
+    const int32_t id = isp ? pos_i[c] : k.neg[static_cast<int64_t>(i) * k.n_neg + (c - k.k_p)];
+    bool ok = id >= 0 && id < k.L;
+    if (!isp || k.softmax) {
+        bool hit = false, any_pos = false;
+        for (int q = 0; q < k.k_p; ++q) {
+            const int32_t pq = pos_i[q];
+            hit = hit || pq == id;
+            any_pos = any_pos || (pq >= 0 && pq < k.L);
+        }
+        if (!isp && hit) ok = false;
+        if (k.softmax && !any_pos) ok = false;
+    }
+    return ok ? static_cast<uint32_t>(id) : static_cast<uint32_t>(k.L);
+}
+
+// MAKE: this is the first kernel of the step; it forms the (key, pair index) pairs, writes them to `pairs_out`
+// and counts their digits.  Otherwise the pairs are read.
+template <bool MAKE>
 __global__ __launch_bounds__(256)
 void radix_count_kernel(const uint2* __restrict__ pairs, int64_t P, int64_t chunk, int shift, int rb,
-                        int nb, int* __restrict__ counts /* [radix][nb] */, uint32_t inv_key, int inv_digit) {
+                        int nb, int* __restrict__ counts /* [radix][nb] */, uint32_t inv_key, int inv_digit,
+                        const KeySource ks, uint2* __restrict__ pairs_out, int32_t* __restrict__ stats) {
     __shared__ int hist[kMaxRadix];
     const int radix = 1 << rb;
     for (int d = threadIdx.x; d < radix; d += 256) hist[d] = 0;
+    if (MAKE && blockIdx.x == 0 && threadIdx.x == 0) stats[0] = 0;      // rows updated inside the gather: counted later
     __syncthreads();
     const int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
     p1 = p1 < P ? p1 : P;
-    for (int64_t p = p0 + threadIdx.x; p < p1; p += 256)
-        atomicAdd(&hist[digit_of(pairs[p].x, shift, radix, inv_key, inv_digit)], 1);
+    for (int64_t p = p0 + threadIdx.x; p < p1; p += 256) {
+        uint32_t key;
+        if (MAKE) {
+            key = pair_key(ks, static_cast<uint32_t>(p));
+            pairs_out[p] = make_uint2(key, static_cast<uint32_t>(p));
+        } else {
+            key = pairs[p].x;
+        }
+        atomicAdd(&hist[digit_of(key, shift, radix, inv_key, inv_digit)], 1);
+    }
     __syncthreads();
     for (int d = threadIdx.x; d < radix; d += 256) counts[d * nb + blockIdx.x] = hist[d];
 }
@@ -588,7 +673,8 @@ __global__ __launch_bounds__(kSortTile)
 void bucket_sort_kernel(const uint2* __restrict__ in, uint2* __restrict__ out,
                         const int* __restrict__ sizes /* [gridDim.x] pairs per bucket */,
                         const int* __restrict__ bases /* [gridDim.x] first pair of each bucket */, int rb,
-                        int* __restrict__ head_cnt /* [gridDim.x] */) {
+                        int* __restrict__ head_cnt /* [gridDim.x] */,
+                        int* __restrict__ multi_cnt /* [gridDim.x] labels of the bucket with several pairs */) {
     extern __shared__ int sort_lds[];                  // offs[radix], whist[waves][radix]: sized by the launch
     __shared__ int wsum[kSortTile / kWave];
     __shared__ int red[kSortTile / kWave];
@@ -625,11 +711,11 @@ void bucket_sort_kernel(const uint2* __restrict__ in, uint2* __restrict__ out,
     {   // bins -> start positions (exclusive scan, contiguous bins per thread); heads = non-empty bins
         const int per = (radix + kSortTile - 1) / kSortTile;        // <= 8
         int cnt[kMaxRadix / kSortTile];
-        int local = 0, nz = 0;
+        int local = 0, nz = 0, nz2 = 0;
         for (int j = 0; j < per; ++j) {
             const int d = tid * per + j;
             const int c = d < radix ? offs[d] : 0;
-            cnt[j] = c; local += c; nz += c > 0 ? 1 : 0;
+            cnt[j] = c; local += c; nz += c > 0 ? 1 : 0; nz2 += c > 1 ? 1 : 0;
         }
         const int incl = wave_incl_scan(local);
         if ((tid & 63) == 63) wsum[wave] = incl;
@@ -641,7 +727,8 @@ void bucket_sort_kernel(const uint2* __restrict__ in, uint2* __restrict__ out,
             if (d < radix) { offs[d] = run; run += cnt[j]; }
         }
         const int heads = block_sum<int, kSortTile / kWave>(nz, red);
-        if (tid == 0) head_cnt[b] = heads;
+        const int multis = block_sum<int, kSortTile / kWave>(nz2, red);
+        if (tid == 0) { head_cnt[b] = heads; multi_cnt[b] = multis; }
     }
     if (in_regs) {
 #pragma unroll
@@ -675,19 +762,22 @@ __device__ __forceinline__ bool is_head(const uint2* pairs, int64_t p, uint32_t 
 
 __global__ __launch_bounds__(256)
 void heads_count_kernel(const uint2* __restrict__ pairs, int64_t P, int64_t chunk, uint32_t Lkey,
-                        int* __restrict__ head_cnt, int* __restrict__ valid_cnt) {
+                        int* __restrict__ head_cnt, int* __restrict__ valid_cnt, int* __restrict__ multi_cnt) {
     __shared__ int sh[4];
     const int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
     p1 = p1 < P ? p1 : P;
-    int h = 0, v = 0;
+    int h = 0, v = 0, m = 0;
     for (int64_t p = p0 + threadIdx.x; p < p1; p += 256) {
-        h += is_head(pairs, p, Lkey) ? 1 : 0;
+        const bool head = is_head(pairs, p, Lkey);
+        h += head ? 1 : 0;
+        m += (head && p + 1 < P && pairs[p + 1].x == pairs[p].x) ? 1 : 0;      // a label with several pairs
         v += pairs[p].x < Lkey ? 1 : 0;
     }
     h = block_sum<int, 4>(h, sh);
     v = block_sum<int, 4>(v, sh);
-    if (threadIdx.x == 0) { head_cnt[blockIdx.x] = h; valid_cnt[blockIdx.x] = v; }
+    m = block_sum<int, 4>(m, sh);
+    if (threadIdx.x == 0) { head_cnt[blockIdx.x] = h; valid_cnt[blockIdx.x] = v; multi_cnt[blockIdx.x] = m; }
 }
 
 __global__ __launch_bounds__(256)
@@ -695,59 +785,78 @@ void heads_write_kernel(const uint2* __restrict__ pairs, int64_t P, int64_t chun
                         int nb, const int* __restrict__ head_cnt, const int* __restrict__ valid_cnt,
                         int32_t* __restrict__ touched,
                         int32_t* __restrict__ seg_start, uint32_t* __restrict__ seg_idx0,
-                        int32_t* __restrict__ n_touched, const float* __restrict__ loss_q, int64_t B,
-                        float inv_B, float* __restrict__ loss, int SQ,
+                        int32_t* __restrict__ n_touched,
                         const int* __restrict__ bucket_sizes /* not null: block b covers bucket b ... */,
-                        const int* __restrict__ bucket_bases /* ... which starts at pair bucket_bases[b] */) {
+                        const int* __restrict__ bucket_bases /* ... which starts at pair bucket_bases[b] */,
+                        int32_t* __restrict__ single_slot /* [P] by pair index, or null */,
+                        const int* __restrict__ multi_cnt, int32_t* __restrict__ multi_list /* segments with several pairs */,
+                        int32_t* __restrict__ stats) {
     __shared__ int sh[4];
-    __shared__ float shf[4];
-    __shared__ int wcnt[4];
-    __shared__ int running;
+    __shared__ int wcnt[4], wcnt_m[4];
+    __shared__ int running, running_m;
     const int tid = threadIdx.x;
     if (static_cast<int>(blockIdx.x) == nb) {
-        // one workgroup beyond those of the keys: the totals and the loss, off the other workgroups' path
-        int th = 0, tv = 0;
-        for (int b = tid; b < nb; b += 256) { th += head_cnt[b]; tv += valid_cnt[b]; }
+        // one workgroup beyond those of the keys: the totals, off the other workgroups' path
+        int th = 0, tv = 0, tm = 0;
+        for (int b = tid; b < nb; b += 256) { th += head_cnt[b]; tv += valid_cnt[b]; tm += multi_cnt[b]; }
         th = block_sum<int, 4>(th, sh);
         tv = block_sum<int, 4>(tv, sh);
-        if (tid == 0) { n_touched[0] = th; seg_start[th] = tv; }
-        // loss = (1/B) sum_i loss_q[i], summed in a fixed order
-        float t2 = 0.0f;
-        for (int64_t i = tid; i < B * SQ; i += 256) t2 += loss_q[i];
-        t2 = block_sum<float, 4>(t2, shf);
-        if (tid == 0) loss[0] = t2 * inv_B;
+        tm = block_sum<int, 4>(tm, sh);
+        if (tid == 0) { n_touched[0] = th; seg_start[th] = tv; stats[1] = tm; }
         return;
     }
     int bucket_p0 = 0, bucket_n = 0;
     if (bucket_sizes) { bucket_p0 = bucket_bases[blockIdx.x]; bucket_n = bucket_sizes[blockIdx.x]; }
     // heads in the blocks before this one
-    int t = 0;
-    for (int b = tid; b < static_cast<int>(blockIdx.x); b += 256) t += head_cnt[b];
+    int t = 0, tm = 0;
+    for (int b = tid; b < static_cast<int>(blockIdx.x); b += 256) { t += head_cnt[b]; tm += multi_cnt[b]; }
     t = block_sum<int, 4>(t, sh);
-    if (tid == 0) running = t;
+    tm = block_sum<int, 4>(tm, sh);
+    if (tid == 0) { running = t; running_m = tm; }
     __syncthreads();
     int64_t p0 = blockIdx.x * chunk;
     int64_t p1 = p0 + chunk;
     if (bucket_sizes) { p0 = bucket_p0; p1 = p0 + bucket_n; }
     p1 = p1 < P ? p1 : P;
+    int singles = 0;
     for (int64_t t0 = p0; t0 < p1; t0 += 256) {
         const int64_t p = t0 + tid;
         const bool head = p < p1 && is_head(pairs, p, Lkey);
+        uint2 kv = make_uint2(0u, 0u);
+        if (p < p1) kv = pairs[p];
+        const bool single = head && (p + 1 >= P || pairs[p + 1].x != kv.x);
         const uint64_t bal = __ballot(head);
-        if ((tid & 63) == 0) wcnt[tid >> 6] = __popcll(bal);
+        const uint64_t bal_m = __ballot(head && !single);
+        if ((tid & 63) == 0) { wcnt[tid >> 6] = __popcll(bal); wcnt_m[tid >> 6] = __popcll(bal_m); }
         lds_barrier();
-        int before = running;
-        for (int w = 0; w < (tid >> 6); ++w) before += wcnt[w];
-        if (head) {
+        int before = running, before_m = running_m;
+        for (int w = 0; w < (tid >> 6); ++w) { before += wcnt[w]; before_m += wcnt_m[w]; }
+        if (p < p1) {
             const int s = before + __popcll(bal & lanemask_lt());
-            const uint2 kv = pairs[p];
-            touched[s] = static_cast<int32_t>(kv.x);
-            seg_start[s] = static_cast<int32_t>(p);
-            seg_idx0[s] = kv.y;                  // first pair of the segment, saves the update a hop
+            if (head) {
+                touched[s] = static_cast<int32_t>(kv.x);
+                seg_start[s] = static_cast<int32_t>(p);
+                seg_idx0[s] = kv.y;                  // first pair of the segment, saves the update a hop
+            }
+            if (single_slot != nullptr) {
+                // a label with one pair only: the gather updates its row itself and needs the row's place in the
+                // touched list (for the copy of the updated rows); every other pair is told -1.  The other
+                // labels are listed for the row update kernel.
+                single_slot[kv.y] = single ? s : -1;
+                singles += single ? 1 : 0;
+                if (head && !single) multi_list[before_m + __popcll(bal_m & lanemask_lt())] = s;
+            }
         }
         lds_barrier();
-        if (tid == 0) running += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+        if (tid == 0) {
+            running += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+            running_m += wcnt_m[0] + wcnt_m[1] + wcnt_m[2] + wcnt_m[3];
+        }
         lds_barrier();
+    }
+    if (single_slot != nullptr) {
+        singles = block_sum<int, 4>(singles, sh);
+        if (tid == 0 && singles > 0) atomicAdd(&stats[0], singles);      // an integer sum: the same in every run
     }
 }
 
@@ -772,19 +881,33 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
                    const int32_t* __restrict__ touched, const int32_t* __restrict__ seg_start,
                    const uint32_t* __restrict__ seg_idx0, const int32_t* __restrict__ n_touched, float lr,
                    T* __restrict__ rows_out,
-                   const float* __restrict__ dz_part, int SQ, int64_t BD, float* __restrict__ dZ) {
+                   const float* __restrict__ dz_part, int SQ, int64_t BD, float* __restrict__ dZ,
+                   const int32_t* __restrict__ multi_list /* not null: labels with one pair were updated by the gather,
+                                                             these are the segments left, n_multi[0] of them */,
+                   const int32_t* __restrict__ n_multi,
+                   const float* __restrict__ loss_q, int64_t n_loss, float inv_B, float* __restrict__ loss) {
     constexpr int EPC = Elem<T>::kPerChunk;
     constexpr int U = 2;
     extern __shared__ float lpart[];              // [NG][CPL][G][EPC] partial sums of a long segment
     __shared__ int long_q[kMaxGroups * kLongPerGroup];   // [group][slot]
     __shared__ int long_n[kMaxGroups];                    // slots filled by each group
     const int tid = threadIdx.x;
+    if (blockIdx.x == gridDim.x - 1) {
+        // one workgroup beyond those of the rows: loss = (1/B) sum of the gather's partial losses, in a fixed order
+        __shared__ float shf[kStepThreads / kWave];
+        float t2 = 0.0f;
+        for (int64_t i = tid; i < n_loss; i += kStepThreads) t2 += loss_q[i];
+        t2 = block_sum<float, kStepThreads / kWave>(t2, shf);
+        if (tid == 0) loss[0] = t2 * inv_B;
+        return;
+    }
+    const int n_wg = gridDim.x - 1;                       // workgroups that share the rows
     int my_long = 0;                                      // uniform within the group
     // dZ = sum of the partials written by the workgroups that shared a query, in split order
     // (independent of the row updates below; done here because this grid is large)
     if (SQ > 1) {
         for (int64_t e = static_cast<int64_t>(blockIdx.x) * kStepThreads + tid; e < BD;
-             e += static_cast<int64_t>(gridDim.x) * kStepThreads) {
+             e += static_cast<int64_t>(n_wg) * kStepThreads) {
             float v = dz_part[e];
             for (int q = 1; q < SQ; ++q) v += dz_part[q * BD + e];
             dZ[e] = v;
@@ -795,7 +918,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
     const int nchunks = d / EPC;
     const int64_t row_bytes = static_cast<int64_t>(d) * sizeof(T);
     const unsigned char* Zb = reinterpret_cast<const unsigned char*>(Z);
-    const int64_t n_seg = n_touched[0];
+    const int64_t n_seg = multi_list != nullptr ? n_multi[0] : n_touched[0];
     // pair index -> query row: exact division by n through a multiply-high (n_magic, n_shift
     // from the host; valid for every index below 2^31)
     auto query_of = [&](uint32_t idx) -> int64_t {
@@ -806,8 +929,10 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
     // A group walks several segments so that waves live long enough to keep the chip full.  The
     // loads run ahead of the arithmetic: hop 1 (what identifies a segment) two segments ahead,
     // hop 2 (the row of W, the coefficient and the query row of the first pair) one ahead.
-    struct Hop1 { int p0, p1, label; uint32_t idx0; };
-    auto load_hop1 = [&](int64_t sx, Hop1& h) {
+    struct Hop1 { int p0, p1, label, seg; uint32_t idx0; };
+    auto load_hop1 = [&](int64_t sl, Hop1& h) {
+        const int64_t sx = multi_list != nullptr ? multi_list[sl] : sl;      // position in the touched list
+        h.seg = static_cast<int>(sx);
         h.p0 = seg_start[sx]; h.p1 = seg_start[sx + 1]; h.label = touched[sx]; h.idx0 = seg_idx0[sx];
     };
     auto load_hop2 = [&](const Hop1& h, uint4 (&wv)[CPL], uint4 (&z0)[CPL], float& g0) {
@@ -825,9 +950,9 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
             }
         }
     };
-    const int64_t s_step = static_cast<int64_t>(gridDim.x) * NG;
+    const int64_t s_step = static_cast<int64_t>(n_wg) * NG;
     int64_t s = static_cast<int64_t>(blockIdx.x) * NG + tid / G;
-    Hop1 h_n = {0, 0, 0, 0u}, h_nn = {0, 0, 0, 0u};
+    Hop1 h_n = {0, 0, 0, 0, 0u}, h_nn = {0, 0, 0, 0, 0u};
     uint4 wv_n[CPL], z0_n[CPL];
     float g0_n = 0.0f;
 #pragma unroll
@@ -841,7 +966,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
     uint4 wv[CPL], z0[CPL];
 #pragma unroll
     for (int j = 0; j < CPL; ++j) { wv[j] = wv_n[j]; z0[j] = z0_n[j]; }
-    const int64_t s_cur = s;
+    const int64_t s_cur = h_n.seg;                // position in the touched list
     if (s + s_step < n_seg) { h_n = h_nn; load_hop2(h_n, wv_n, z0_n, g0_n); }
     if (s + 2 * s_step < n_seg) load_hop1(s + 2 * s_step, h_nn);
     if (p1 - p0 > kLongSeg && my_long < kLongPerGroup) {        // uniform within the group
@@ -902,7 +1027,7 @@ void update_kernel(const T* __restrict__ Z, T* __restrict__ W, int d, uint32_t n
             }
         }
     }
-    unsigned char* orow = rows_out ? reinterpret_cast<unsigned char*>(rows_out) + s * row_bytes : nullptr;
+    unsigned char* orow = rows_out ? reinterpret_cast<unsigned char*>(rows_out) + s_cur * row_bytes : nullptr;
 #pragma unroll
     for (int j = 0; j < CPL; ++j) {
         const int ch = gl + j * G;
@@ -1021,7 +1146,7 @@ struct StepPlan {
     bool stream_update, stream_gather;      // rows of W go through the caches with the non-temporal hint
     uint32_t n_magic;
     int64_t chunk;
-    size_t off_pairs0, off_pairs1, off_g, off_lossq, off_dzpart, off_counts, off_totals, off_bases, off_headcnt,
+    size_t off_stats, off_single, off_multi, off_multicnt, off_pairs0, off_pairs1, off_g, off_lossq, off_dzpart, off_counts, off_totals, off_bases, off_headcnt,
         off_validcnt, off_segstart, off_segidx0, total;
 };
 
@@ -1096,6 +1221,7 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     size_t off = 0;
     auto take = [&off](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
     const size_t P = static_cast<size_t>(p->P);
+    p->off_stats = take(256);                  // word 0: rows updated inside the gather (labels with one pair)
     p->off_pairs0 = take(P * 8); p->off_pairs1 = take(P * 8);
     p->off_g = take(P * 4);
     // few queries: several workgroups share a query so that the chip is filled
@@ -1109,21 +1235,31 @@ static int plan_step(int64_t B, int64_t L, int d, int k_p, int n_neg, xc_dtype t
     p->off_validcnt = take(static_cast<size_t>(kSortMaxBlocks) * 4);
     p->off_segstart = take((P + 1) * 4);
     p->off_segidx0 = take(P * 4);
+    p->off_single = take(P * 4);
+    p->off_multi = take(P * 4);
+    p->off_multicnt = take(static_cast<size_t>(kSortMaxBlocks > kMaxRadix ? kSortMaxBlocks : kMaxRadix) * 4);
     p->total = off;
     return XC_OK;
 }
 
 template <typename T, int KIND>
-static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, const void* W, int64_t B,
+static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, void* W, int64_t B,
                           int64_t L, int d, const int32_t* pos, int k_p, const int32_t* neg,
-                          const float* logq, int n_neg, uint2* pairs, float* gco,
-                          float* loss_q, float* dZ, int SQ) {
+                          const float* logq, int n_neg, const int32_t* single_slot /* null: no row updates here */,
+                          float lr, void* rows_out, float* gco, float* loss_q, float* dZ, int SQ) {
     const float inv_B = 1.0f / static_cast<float>(B);
     const dim3 grid(static_cast<unsigned>(B * SQ));
+    // (the soft-max coefficient needs the whole query first: no fused row updates there)
+    const bool fuse = KIND == XC_LOSS_BCE && single_slot != nullptr;
+#define XC_GATHER3(CPL, UU, FF, SS, FU)                                                                \
+    XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, UU, FF, SS, FU><<<grid, kStepThreads, 0, st>>>( \
+        static_cast<const T*>(Z), static_cast<T*>(W), L, d, pos, k_p, neg, logq, n_neg,                \
+        pl.G, SQ, B, inv_B, single_slot, lr, static_cast<T*>(rows_out), gco, loss_q, dZ)))
 #define XC_GATHER2(CPL, UU, FF, SS)                                                                    \
-    XC_LAUNCH(K_GATHER, st, (gather_kernel<T, CPL, KIND, UU, FF, SS><<<grid, kStepThreads, 0, st>>>(     \
-        static_cast<const T*>(Z), static_cast<const T*>(W), L, d, pos, k_p, neg, logq, n_neg,          \
-        pl.G, SQ, B, inv_B, pairs, gco, loss_q, dZ)))
+    do {                                                                                               \
+        if (KIND == XC_LOSS_BCE && fuse) XC_GATHER3(CPL, UU, FF, SS, (KIND == XC_LOSS_BCE));           \
+        else XC_GATHER3(CPL, UU, FF, SS, false);                                                       \
+    } while (0)
 #define XC_GATHER(CPL)                                                                                 \
     do {                                                                                               \
         const bool full = (d / Elem<T>::kPerChunk) == pl.G * CPL && d % Elem<T>::kPerChunk == 0;       \
@@ -1143,6 +1279,7 @@ static void launch_gather(const StepPlan& pl, hipStream_t st, const void* Z, con
     }
 #undef XC_GATHER
 #undef XC_GATHER2
+#undef XC_GATHER3
 }
 
 template <typename T>
@@ -1150,18 +1287,19 @@ static void launch_update(const StepPlan& pl, hipStream_t st, const void* Z, voi
                           const uint2* pairs, const float* gco, const int32_t* touched,
                           const int32_t* seg_start, const uint32_t* seg_idx0, const int32_t* n_touched,
                           float lr, void* rows_out,
-                          const float* dz_part, int SQ, int64_t BD, float* dZ) {
+                          const float* dz_part, int SQ, int64_t BD, float* dZ, const int32_t* multi_list,
+                          const int32_t* n_multi, const float* loss_q, int64_t n_loss, float inv_B, float* loss) {
     const int NG = kStepThreads / pl.G;
     // a pair per group would need P/NG workgroups; with several segments per group the grid is
     // bounded by what the chip holds at once
     int64_t nwg = (pl.P + NG - 1) / NG;
     if (nwg > kUpdateMaxGrid) nwg = kUpdateMaxGrid;
-    const dim3 grid(static_cast<unsigned>(nwg));
+    const dim3 grid(static_cast<unsigned>(nwg + 1));       // one more for the loss
 #define XC_UPDATE2(CPL, SS)                                                                       \
     XC_LAUNCH(K_UPDATE, st, (update_kernel<T, CPL, SS><<<grid, kStepThreads,                      \
         kStepThreads * CPL * Elem<T>::kPerChunk * sizeof(float), st>>>(                             \
         static_cast<const T*>(Z), static_cast<T*>(W), d, pl.n_magic, pl.n_shift, pl.G, pairs, gco, touched, seg_start, \
-        seg_idx0, n_touched, lr, static_cast<T*>(rows_out), dz_part, SQ, BD, dZ)))
+        seg_idx0, n_touched, lr, static_cast<T*>(rows_out), dz_part, SQ, BD, dZ, multi_list, n_multi, loss_q, n_loss, inv_B, loss)))
 #define XC_UPDATE(CPL)                                                                            \
     do { if (pl.stream_update) XC_UPDATE2(CPL, true); else XC_UPDATE2(CPL, false); } while (0)
     switch (pl.cpl) {
@@ -1231,55 +1369,74 @@ static int step_impl(const void* Z, void* W, int64_t B, int64_t L, int d, const 
     int32_t* seg_start = reinterpret_cast<int32_t*>(w8 + pl.off_segstart);
     uint32_t* seg_idx0 = reinterpret_cast<uint32_t*>(w8 + pl.off_segidx0);
 
-    // S3 + S4
-    const int SQ = kind == XC_LOSS_BCE ? pl.sq : 1;      // the soft-max normaliser needs the whole query
-    float* dz_target = SQ > 1 ? reinterpret_cast<float*>(w8 + pl.off_dzpart) : dZ;
-    if (t == XC_BF16) {
-        if (kind == XC_LOSS_BCE)
-            launch_gather<bf16_t, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, pairs0, gco, loss_q, dz_target, SQ);
-        else
-            launch_gather<bf16_t, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, pairs0, gco, loss_q, dz_target, SQ);
-    } else {
-        if (kind == XC_LOSS_BCE)
-            launch_gather<float, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, pairs0, gco, loss_q, dz_target, SQ);
-        else
-            launch_gather<float, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, pairs0, gco, loss_q, dz_target, SQ);
-    }
-    XC_HIP_CHECK(hipGetLastError());
+    int32_t* stats = reinterpret_cast<int32_t*>(w8 + pl.off_stats);
+    int32_t* single_slot = reinterpret_cast<int32_t*>(w8 + pl.off_single);
+    int32_t* multi_list = reinterpret_cast<int32_t*>(w8 + pl.off_multi);
+    int* multi_cnt = reinterpret_cast<int*>(w8 + pl.off_multicnt);
+    // Labels with one pair are updated inside the gather where they are the rule: with P pairs spread over L
+    // labels the share of touched labels that have one pair is about exp(-P/L), and the gather pays for each of
+    // them with a row written from a kernel that is bound by instruction issue.  Measured: 2.3 M pairs over
+    // 1.3 M labels (a third single) loses 8 % of the step, 8.6 M over 120 M (96 % single) gains 30 %.
+    const bool fuse = kind == XC_LOSS_BCE && 2 * pl.P <= L;
+    KeySource ks;
+    ks.pos = pos; ks.neg = neg; ks.k_p = k_p; ks.n_neg = n_neg; ks.n = pl.n; ks.n_shift = pl.n_shift;
+    ks.n_magic = pl.n_magic; ks.softmax = kind == XC_LOSS_SOFTMAX ? 1 : 0; ks.L = L;
 
-    // S5: sort pairs by label
+    // S5, first half: the pairs sorted by label and the segment heads.  They depend on the ids alone, so they come
+    // first, and the gather that follows knows which rows it may update itself.
     uint2 *kin = pairs0, *kout = pairs1;
     if (pl.n_buckets > 0) {
         // one round on the high digit (masked pairs behind every label), then each bucket by its low digit
         const int radix = 1 << pl.high_rb;
         const uint32_t Lk = static_cast<uint32_t>(L);
-        XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, Lk, pl.n_buckets)));
+        XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<true><<<pl.nb, 256, 0, st>>>(nullptr, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, Lk, pl.n_buckets, ks, kin, stats)));
         XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
         XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.high_rb), st>>>(kin, kout, pl.P, pl.chunk, pl.low_bits, pl.high_rb, pl.nb, counts, totals, Lk, pl.n_buckets, bases)));
-        XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, sort_lds_bytes(pl.low_bits), st>>>(kout, kin, totals, bases, pl.low_bits, head_cnt)));
+        XC_LAUNCH(K_BUCKET_SORT, st, (bucket_sort_kernel<<<pl.n_buckets, kSortTile, sort_lds_bytes(pl.low_bits), st>>>(kout, kin, totals, bases, pl.low_bits, head_cnt, multi_cnt)));
         // the sizes of the label buckets add up to the number of unmasked pairs
         XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.n_buckets + 1, 256, 0, st>>>(kin, pl.P, pl.chunk, Lk, pl.n_buckets, head_cnt,
-                                                                                     totals, touched, seg_start, seg_idx0, n_touched, loss_q, B,
-                                                                                     1.0f / static_cast<float>(B), loss, SQ, totals, bases)));
+                                                                                     totals, touched, seg_start, seg_idx0, n_touched, totals, bases,
+                                                                                     fuse ? single_slot : nullptr, multi_cnt, multi_list, stats)));
         XC_HIP_CHECK(hipGetLastError());
     } else {
         for (int pass = 0; pass < pl.passes; ++pass) {
             const int shift = pass * pl.rb;
             const int radix = 1 << pl.rb;
-            XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, 0xffffffffu, 0)));
+            if (pass == 0) XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<true><<<pl.nb, 256, 0, st>>>(nullptr, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, 0xffffffffu, 0, ks, kin, stats)));
+            else XC_LAUNCH(K_RADIX_COUNT, st, (radix_count_kernel<false><<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, 0xffffffffu, 0, ks, nullptr, stats)));
             XC_LAUNCH(K_RADIX_SCAN, st, (radix_prefix_kernel<<<radix, kWave, 0, st>>>(counts, pl.nb, totals)));
             XC_LAUNCH(K_RADIX_SCATTER, st, (radix_scatter_kernel<<<pl.nb, kSortTile, sort_lds_bytes(pl.rb), st>>>(kin, kout, pl.P, pl.chunk, shift, pl.rb, pl.nb, counts, totals, 0xffffffffu, 0, nullptr)));
             XC_HIP_CHECK(hipGetLastError());
             uint2* tk = kin; kin = kout; kout = tk;
         }
-        XC_LAUNCH(K_HEADS_COUNT, st, (heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt)));
+        XC_LAUNCH(K_HEADS_COUNT, st, (heads_count_kernel<<<pl.nb, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), head_cnt, valid_cnt, multi_cnt)));
         XC_LAUNCH(K_HEADS_WRITE, st, (heads_write_kernel<<<pl.nb + 1, 256, 0, st>>>(kin, pl.P, pl.chunk, static_cast<uint32_t>(L), pl.nb, head_cnt,
-                                                                                valid_cnt, touched, seg_start, seg_idx0, n_touched, loss_q, B,
-                                                                                1.0f / static_cast<float>(B), loss, SQ, nullptr, nullptr)));
+                                                                                valid_cnt, touched, seg_start, seg_idx0, n_touched, nullptr, nullptr,
+                                                                                fuse ? single_slot : nullptr, multi_cnt, multi_list, stats)));
         XC_HIP_CHECK(hipGetLastError());
     }
-    if (t == XC_BF16) launch_update<bf16_t>(pl, st, Z, W, d, kin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
-    else launch_update<float>(pl, st, Z, W, d, kin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ);
+
+    // S3 + S4 (+ the row update of every label with a single pair)
+    const int SQ = kind == XC_LOSS_BCE ? pl.sq : 1;      // the soft-max normaliser needs the whole query
+    float* dz_target = SQ > 1 ? reinterpret_cast<float*>(w8 + pl.off_dzpart) : dZ;
+    if (t == XC_BF16) {
+        if (kind == XC_LOSS_BCE)
+            launch_gather<bf16_t, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, fuse ? single_slot : nullptr, lr, W_rows_out, gco, loss_q, dz_target, SQ);
+        else
+            launch_gather<bf16_t, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, fuse ? single_slot : nullptr, lr, W_rows_out, gco, loss_q, dz_target, SQ);
+    } else {
+        if (kind == XC_LOSS_BCE)
+            launch_gather<float, XC_LOSS_BCE>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, fuse ? single_slot : nullptr, lr, W_rows_out, gco, loss_q, dz_target, SQ);
+        else
+            launch_gather<float, XC_LOSS_SOFTMAX>(pl, st, Z, W, B, L, d, pos, k_p, neg, logq, n_neg, fuse ? single_slot : nullptr, lr, W_rows_out, gco, loss_q, dz_target, SQ);
+    }
+    XC_HIP_CHECK(hipGetLastError());
+
+    // S5, second half: the rows of the labels with several pairs
+    const int64_t n_loss = B * SQ;
+    const float inv_B = 1.0f / static_cast<float>(B);
+    if (t == XC_BF16) launch_update<bf16_t>(pl, st, Z, W, d, kin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ, fuse ? multi_list : nullptr, stats + 1, loss_q, n_loss, inv_B, loss);
+    else launch_update<float>(pl, st, Z, W, d, kin, gco, touched, seg_start, seg_idx0, n_touched, lr, W_rows_out, dz_target, SQ, B * static_cast<int64_t>(d), dZ, fuse ? multi_list : nullptr, stats + 1, loss_q, n_loss, inv_B, loss);
     XC_HIP_CHECK(hipGetLastError());
     return XC_OK;
 }

@@ -71,6 +71,11 @@ def _run_and_check(Z, W, pos, neg, logq, Z64, W64, lr, kind):
     (48, 20000, 768, torch.bfloat16, 4, 64, 256),     # config-2 row shape
     (16, 9000, 256, torch.bfloat16, 3, 50, 300),      # config-5 row shape
     (9, 2000, 2048, torch.bfloat16, 2, 8, 24),        # longest supported row
+    # few pairs for the number of labels (2 P <= L): most labels have one pair and get their row updated inside
+    # the gather (BCE), the others are listed for the row update kernel
+    (64, 200000, 256, torch.bfloat16, 3, 50, 300),    # config-5 row shape
+    (40, 150000, 768, torch.bfloat16, 4, 64, 256),
+    (33, 90000, 72, torch.bfloat16, 3, 5, 40),        # ragged rows
 ])
 def test_step_matches_oracle(B, L, d, dtype, k_p, k_h, k_r, kind):
     print("case", B, L, d, dtype, k_p, k_h, k_r, kind, flush=True)
@@ -124,9 +129,10 @@ def test_step_without_negatives_or_without_positives():
     _run_and_check(Z, W, np.full((B, 2), -1, np.int32), neg, logq, Z64, W64, 0.1, orc.LOSS_SOFTMAX)
 
 
-def test_step_is_bitwise_reproducible():
+@pytest.mark.parametrize("L", [1000, 60000])              # row updates by the update kernel alone / mostly inside the gather
+def test_step_is_bitwise_reproducible(L):
     import paper_2409_20156_amd as xc
-    Z, W, pos, neg, logq, _, _ = _inputs(8, 40, 1000, 768, torch.bfloat16, 4, 16, 100)
+    Z, W, pos, neg, logq, _, _ = _inputs(8, 40, L, 768, torch.bfloat16, 4, 16, 100)
     dev = Z.device
     res = []
     for _ in range(2):
