@@ -277,6 +277,79 @@ def sample_negatives_mixture(shortlist, scores, B: int, M: int, k_h: int, k_r: i
     return neg, logq
 
 
+def pps_select(w, k: int, u: int):
+    """k of the slots with weight w[m] > 0, without replacement, slot m included with probability
+    proportional to its weight: pi_m = min(1, k' w_m / T') exactly.  Two steps.
+    (1) Certain slots: while some remaining slot has k' w_m >= T' (k' slots still to choose, T' the
+        remaining total weight), all such slots are taken at once, k' and T' shrink, and the test is
+        repeated.
+    (2) Systematic sampling of the rest (Madow 1949): on the axis of the running sums c_m of the
+        remaining weights in slot order, scaled by k', the k' points U + j T' (j = 0..k'-1) are marked,
+        U = floor(u T' / 2^64) uniform on 0..T'-1; slot m is taken if a point falls into
+        [k' c_{m-1}, k' c_m).  Every such interval is shorter than T', so no slot is taken twice, exactly
+        k' are taken, and of the T' equally likely offsets exactly k' w_m take slot m.
+    Returns (taken slots in slot order, pi as a list of (numerator, denominator) per slot; (0, 1) for
+    weightless slots).  Needs 1 <= k <= number of slots with weight."""
+    M = len(w)
+    state = [1 if w[m] > 0 else 0 for m in range(M)]          # 1 remaining, 2 certain
+    kk, TT = k, sum(w)
+    while True:
+        sure = [m for m in range(M) if state[m] == 1 and kk * w[m] >= TT]
+        if not sure:
+            break
+        for m in sure:
+            state[m] = 2
+        kk -= len(sure)
+        TT -= sum(w[m] for m in sure)
+    pi = [(1, 1) if state[m] == 2 else ((kk * w[m], TT) if state[m] == 1 else (0, 1)) for m in range(M)]
+    taken = [m for m in range(M) if state[m] == 2]
+    if kk > 0:
+        U = bounded(u, TT)
+
+        def points_below(x):                                 # number of j in [0, kk) with U + j TT < x
+            return 0 if x <= U else min(kk, (x - U - 1) // TT + 1)
+        c = 0
+        for m in range(M):
+            if state[m] != 1:
+                continue
+            if points_below(kk * (c + w[m])) - points_below(kk * c) == 1:
+                taken.append(m)
+            c += w[m]
+    return sorted(taken), pi
+
+
+def sample_negatives_pps(shortlist, scores, B: int, M: int, k_h: int, k_r: int, L: int, seed: int, rows=None):
+    """Hard negatives SAMPLED from a wider stale shortlist without replacement (Sec. 3.1: the
+    importance distribution proportional to the sigmoid of the stale score, Observation 2, inside the
+    mixture of Idea 2).  Per query: k = min(k_h, slots with weight) shortlist slots are chosen by
+    pps_select with the weights sigmoid_weight(stale score) and the query's draw 0 as random word, and
+    fill slots 0..k-1 in slot order; slots k..k_h+k_r-1 are uniform draws from all of [0, L) (draw j for
+    slot j, as in the other samplers).  logq of a slot = log(expected number of copies of its label)
+      = log(sum of pi_m over the shortlist slots that hold the label + (k_h + k_r - k) / L),
+    so pairs weighted by exp(-logq) estimate a sum over all L labels without bias (a Horvitz-Thompson
+    estimate on the shortlist part).  A row without any weight: all slots uniform.
+    Returns (neg int32 [B, k_h+k_r], logq float32 [B, k_h+k_r])."""
+    n = k_h + k_r
+    neg = np.full((B, n), -1, dtype=np.int32)
+    logq = np.zeros((B, n), dtype=np.float32)
+    for i in (range(B) if rows is None else rows):
+        ids = [int(v) for v in shortlist[i][:M]]
+        w = [sigmoid_weight(scores[i][m]) if 0 <= ids[m] < L else 0 for m in range(M)]
+        nv = sum(1 for x in w if x > 0)
+        k = min(k_h, nv)
+        taken, pi = pps_select(w, k, draw_u64(seed, i, 0)) if k > 0 else ([], [(0, 1)] * M)
+        per_label = {}
+        for m in range(M):                                   # in slot order
+            if pi[m][0]:
+                per_label[ids[m]] = per_label.get(ids[m], np.float64(0.0)) + np.float64(pi[m][0]) / np.float64(pi[m][1])
+        unif = np.float64(n - k) / np.float64(L)
+        for j in range(n):
+            lab = ids[taken[j]] if j < k else bounded(draw_u64(seed, i, j), L)
+            neg[i, j] = lab
+            logq[i, j] = np.float32(np.log(per_label.get(lab, np.float64(0.0)) + unif))
+    return neg, logq
+
+
 # --------------------------------------------------------------------------
 # S3-S5  the sampled training step
 # --------------------------------------------------------------------------

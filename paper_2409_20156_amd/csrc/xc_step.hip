@@ -191,11 +191,6 @@ void gather_kernel(const T* __restrict__ Z, T* W, int64_t L, int d,
         }
     }
 
-    float zf[FUSE ? CPL : 1][EPC];     // the query row once more, unpacked, for the fused row updates
-    if (FUSE) {
-#pragma unroll
-        for (int j = 0; j < (FUSE ? CPL : 1); ++j) Elem<T>::unpack(zp[j], zf[j]);
-    }
     float dz[CPL][EPC];            // BCE: sum g w.  soft-max: sum e^{t-m} w
     float pz[CPL][EPC];            // soft-max only: sum over positives of w
 #pragma unroll
@@ -359,8 +354,14 @@ void gather_kernel(const T* __restrict__ Z, T* W, int64_t L, int d,
                         for (int j = 0; j < CPL; ++j) {
                             const int ch = gl + j * G;
                             if (FULL || ch < nchunks) {
+                                // (unpacked here, and hidden from the compiler's hoisting: kept unpacked for the
+                                // whole loop the query row costs a wave per SIMD)
+                                uint4 zc = zp[j];
+                                asm volatile("" : "+v"(zc.x), "+v"(zc.y), "+v"(zc.z), "+v"(zc.w));
+                                float zf[EPC];
+                                Elem<T>::unpack(zc, zf);
 #pragma unroll
-                                for (int e = 0; e < EPC; ++e) wf[j][e] = fmaf(cg, zf[j][e], wf[j][e]);
+                                for (int e = 0; e < EPC; ++e) wf[j][e] = fmaf(cg, zf[e], wf[j][e]);
                                 const uint4 o = Elem<T>::pack(wf[j]);
                                 store16<STREAM>(wrow + ch * 16, o);
                                 if (orow) store16<STREAM>(orow + ch * 16, o);
