@@ -136,6 +136,33 @@ int xc_sample_negatives_mixture(const int32_t* shortlist /* [B*M] */, const floa
                                 void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Hard negatives SAMPLED WITHOUT REPLACEMENT from a wider stale shortlist, a slot with probability
+ * proportional to the sigmoid of its stale score (Sec. 3.1: the importance distribution of
+ * Observation 2 inside the mixture of Idea 2; the paper then retrieves the top scoring labels
+ * instead, which xc_sample_negatives does).  shortlist and scores are [B*M] as above, weights w_m
+ * as in xc_sample_negatives_mixture.  For query i, k = min(k_h, number of slots with weight) slots
+ * are chosen with inclusion probability pi_m = min(1, k' w_m / T'):
+ *   - slots with k' w_m >= T' (k' slots still to choose, T' the remaining total weight) are taken
+ *     for certain, all at once, and the test is repeated with what remains;
+ *   - the others by systematic sampling: on the axis of the running sums of the remaining weights,
+ *     in slot order and scaled by k', the points U + j T' (j < k') are marked, U = floor(u T' / 2^64)
+ *     with u the query's draw 0; a slot is taken when a point falls into its interval.  No slot is
+ *     taken twice and exactly k' are taken.
+ *   slots 0..k-1     the labels of the chosen slots, in slot order;
+ *   slots k..        independent uniform draws from all of [0,L) (draw j for slot j);
+ *   logq             log(sum of pi_m over the slots holding the label + (k_h + k_r - k) / L): the
+ *                    log of the expected number of copies, so pairs weighted by exp(-logq) estimate
+ *                    the sum over all L labels without bias.  A row without any weight: all slots
+ *                    uniform.
+ * Integer arithmetic only for the ids.  Requires 1 <= M <= XC_MAX_K_SAMPLE, 0 <= k_h <=
+ * XC_MAX_K_SAMPLE, k_h + k_r >= 1.
+ * ------------------------------------------------------------------------- */
+int xc_sample_negatives_pps(const int32_t* shortlist /* [B*M] */, const float* scores /* [B*M] */,
+                            int64_t B, int M, int k_h, int k_r, int64_t L, uint64_t seed,
+                            int32_t* neg /* [B*(k_h+k_r)] out */, float* logq /* [B*(k_h+k_r)] out */,
+                            void* stream);
+
+/* ---------------------------------------------------------------------------
  * One training step of the classifier layer (Alg. 1: scores on positives and
  * sampled negatives, loss of Eq. 2, SGD on W; loss averaged over the batch).
  * Per query i with score s = <z_i, w_l> on the pre-update W:

@@ -6,9 +6,9 @@ include/astra_xc.h).  `binding` marshals torch device tensors into that ABI;
 implementation: calls raise if the library is not built or no GPU is present.
 """
 from .binding import (XC_BF16, XC_F32, XC_LOSS_BCE, XC_LOSS_SOFTMAX, XcError, load_library,
-                      mine_negatives, mine_workspace, sample_negatives, sample_negatives_mixture,
+                      mine_negatives, mine_workspace, sample_negatives, sample_negatives_mixture, sample_negatives_pps,
                       step_workspace, xc_step, xc_step_static)
 
 __all__ = ["XC_BF16", "XC_F32", "XC_LOSS_BCE", "XC_LOSS_SOFTMAX", "XcError", "load_library",
-           "mine_negatives", "mine_workspace", "sample_negatives", "sample_negatives_mixture", "step_workspace",
+           "mine_negatives", "mine_workspace", "sample_negatives", "sample_negatives_mixture", "sample_negatives_pps", "step_workspace",
            "xc_step", "xc_step_static"]

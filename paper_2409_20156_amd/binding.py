@@ -32,6 +32,8 @@ _SIGNATURES = {
     "xc_sample_negatives": (_i32, [_ptr, _i64, _i32, _i32, _i64, _u64, _ptr, _ptr, _ptr]),
     "xc_sample_negatives_mixture": (_i32, [ctypes.c_void_p, ctypes.c_void_p, _i64, _i32, _i32, _i32, _i64,
                                            ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "xc_sample_negatives_pps": (_i32, [ctypes.c_void_p, ctypes.c_void_p, _i64, _i32, _i32, _i32, _i64,
+                                       ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "xc_step_workspace": (_i32, [_i64, _i32, _i32, _i32, _i32, _szp]),
     "xc_profile_enable": (_i32, [_i32]),
     "xc_profile_collect": (_i32, []),
@@ -189,6 +191,27 @@ def sample_negatives_mixture(shortlist: torch.Tensor, scores: torch.Tensor, k_h:
                                            seed & ((1 << 64) - 1), _dev(neg, torch.int32, "neg"),
                                            _dev(logq, torch.float32, "logq"), _stream()),
            "xc_sample_negatives_mixture")
+    return neg, logq
+
+
+def sample_negatives_pps(shortlist: torch.Tensor, scores: torch.Tensor, k_h: int, k_r: int, L: int,
+                         seed: int, *, neg: torch.Tensor | None = None, logq: torch.Tensor | None = None):
+    """neg int32 [B, k_h+k_r], logq fp32: up to k_h slots of the [B, M] shortlist chosen without replacement with
+    probability proportional to the sigmoid of the stale scores, the other slots uniform draws from [0, L)."""
+    lib = load_library()
+    if shortlist.dim() != 2 or scores.shape != shortlist.shape:
+        raise ValueError("shortlist and scores must both be [B, M]")
+    B, M = shortlist.shape
+    n = k_h + k_r
+    if neg is None:
+        neg = torch.empty((B, n), dtype=torch.int32, device=shortlist.device)
+    if logq is None:
+        logq = torch.empty((B, n), dtype=torch.float32, device=shortlist.device)
+    _check(lib.xc_sample_negatives_pps(_dev(shortlist, torch.int32, "shortlist"),
+                                       _dev(scores, torch.float32, "scores"), B, M, k_h, k_r, L,
+                                       seed & ((1 << 64) - 1), _dev(neg, torch.int32, "neg"),
+                                       _dev(logq, torch.float32, "logq"), _stream()),
+           "xc_sample_negatives_pps")
     return neg, logq
 
 

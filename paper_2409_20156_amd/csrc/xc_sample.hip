@@ -231,6 +231,160 @@ void sample_mixture_kernel(const int32_t* __restrict__ shortlist, const float* _
     }
 }
 
+// ---------------------------------------------------------------------------
+// Hard negatives sampled WITHOUT replacement from a wider stale shortlist, slot m with probability
+// proportional to w_m = sigmoid_weight(stale score) (Sec. 3.1, Observation 2, inside the mixture of
+// Idea 2).  k = min(k_h, slots with weight) slots are chosen:
+//   (1) slots with k' w_m >= T' (k' still to choose, T' the remaining weight) are certain; all such
+//       slots are taken at once and the test is repeated with the reduced k', T';
+//   (2) the rest by systematic sampling: the k' points U + j T' on the axis of the running sums of the
+//       remaining weights (slot order) scaled by k', U = floor(u T' / 2^64) from the query's draw 0;
+//       a slot is taken when a point falls into its interval (at most one does: k' w_m < T').
+// pi_m = 1 resp. k' w_m / T' exactly.  Slots k.. of the output are uniform draws from [0, L), and
+// logq = log(sum of pi over the slots holding the label + (k_h + k_r - k) / L).
+// One workgroup per query; integer arithmetic for everything that decides an id.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kSampleThreads)
+void sample_pps_kernel(const int32_t* __restrict__ shortlist, const float* __restrict__ scores, int M,
+                       int k_h, int k_r, int64_t L, uint64_t seed, int n2,
+                       int32_t* __restrict__ neg, float* __restrict__ logq) {
+    __shared__ int32_t ids[XC_MAX_K_SAMPLE];
+    __shared__ uint64_t wts[XC_MAX_K_SAMPLE];
+    __shared__ uint64_t cum[2][XC_MAX_K_SAMPLE];
+    __shared__ uint64_t byid[XC_MAX_K_SAMPLE];
+    __shared__ double pi[XC_MAX_K_SAMPLE];
+    __shared__ int32_t sel[XC_MAX_K_SAMPLE];          // taken slots in slot order
+    __shared__ unsigned char state[XC_MAX_K_SAMPLE];  // 0 no weight, 1 remaining, 2 certain, 3 taken by a point
+    __shared__ uint64_t red_w[kSampleThreads / kWave];
+    __shared__ int red_c[kSampleThreads / kWave];
+    const int64_t i = blockIdx.x;
+    const int n = k_h + k_r;
+    const int tid = threadIdx.x;
+    const int32_t* row = shortlist + i * M;
+    const float* srow = scores + i * M;
+    // sum of (count, weight) over the workgroup, fixed order; every thread gets both
+    auto block_sum2 = [&](int c, uint64_t w, int& c_out, uint64_t& w_out) {
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) { c += __shfl_xor(c, off, kWave); w += __shfl_xor(w, off, kWave); }
+        if ((tid & (kWave - 1)) == 0) { red_c[tid / kWave] = c; red_w[tid / kWave] = w; }
+        __syncthreads();
+        c_out = 0; w_out = 0;
+        for (int q = 0; q < kSampleThreads / kWave; ++q) { c_out += red_c[q]; w_out += red_w[q]; }
+        __syncthreads();
+    };
+    int c_loc = 0;
+    uint64_t w_loc = 0;
+    for (int m = tid; m < n2; m += blockDim.x) {
+        int32_t id = -1;
+        uint64_t w = 0;
+        if (m < M) {
+            id = row[m];
+            if (id >= 0 && id < L) w = sigmoid_weight(srow[m]);
+        }
+        ids[m] = id;
+        wts[m] = w;
+        state[m] = w ? 1 : 0;
+        byid[m] = w ? ((static_cast<uint64_t>(static_cast<uint32_t>(id)) << 32) | static_cast<uint32_t>(m)) : ~0ull;
+        c_loc += w ? 1 : 0;
+        w_loc += w;
+    }
+    int nv;
+    uint64_t TT;
+    block_sum2(c_loc, w_loc, nv, TT);
+    const int k = k_h < nv ? k_h : nv;
+    int kk = k;
+    // (1) certain slots, round by round (each round takes at least one slot or ends the loop)
+    while (kk > 0) {
+        c_loc = 0; w_loc = 0;
+        for (int m = tid; m < n2; m += blockDim.x) {
+            if (state[m] == 1 && static_cast<uint64_t>(kk) * wts[m] >= TT) { state[m] = 2; ++c_loc; w_loc += wts[m]; }
+        }
+        int c_all;
+        uint64_t w_all;
+        block_sum2(c_loc, w_loc, c_all, w_all);
+        if (c_all == 0) break;
+        kk -= c_all;
+        TT -= w_all;
+    }
+    // running sums of the remaining weights in slot order (doubling steps between two buffers)
+    for (int m = tid; m < n2; m += blockDim.x) cum[0][m] = state[m] == 1 ? wts[m] : 0ull;
+    __syncthreads();
+    int cur = 0;
+    for (int off = 1; off < n2; off <<= 1) {
+        for (int m = tid; m < n2; m += blockDim.x)
+            cum[cur ^ 1][m] = cum[cur][m] + (m >= off ? cum[cur][m - off] : 0ull);
+        cur ^= 1;
+        __syncthreads();
+    }
+    // (2) systematic sampling of the remaining slots, and pi of every slot
+    const uint64_t qstate = fmix64(seed ^ (kQueryMul * static_cast<uint64_t>(i + 1)));
+    {
+        const uint64_t U = (kk > 0 && TT > 0) ? __umul64hi(fmix64(qstate + kDrawMul), TT) : 0ull;
+        auto points_below = [&](uint64_t x) -> uint64_t {        // number of j in [0, kk) with U + j TT < x
+            if (x <= U) return 0ull;
+            const uint64_t c = (x - U - 1) / TT + 1;
+            return c < static_cast<uint64_t>(kk) ? c : static_cast<uint64_t>(kk);
+        };
+        for (int m = tid; m < n2; m += blockDim.x) {
+            double p = state[m] == 2 ? 1.0 : 0.0;
+            if (state[m] == 1) {
+                p = static_cast<double>(static_cast<uint64_t>(kk) * wts[m]) / static_cast<double>(TT);
+                if (kk > 0) {
+                    const uint64_t hi = static_cast<uint64_t>(kk) * cum[cur][m];
+                    const uint64_t lo = hi - static_cast<uint64_t>(kk) * wts[m];
+                    if (points_below(hi) - points_below(lo) == 1ull) state[m] = 3;
+                }
+            }
+            pi[m] = p;
+        }
+    }
+    __syncthreads();
+    // taken slots in slot order: positions from a running count (reuses the scan buffers)
+    for (int m = tid; m < n2; m += blockDim.x) cum[0][m] = state[m] >= 2 ? 1ull : 0ull;
+    __syncthreads();
+    cur = 0;
+    for (int off = 1; off < n2; off <<= 1) {
+        for (int m = tid; m < n2; m += blockDim.x)
+            cum[cur ^ 1][m] = cum[cur][m] + (m >= off ? cum[cur][m - off] : 0ull);
+        cur ^= 1;
+        __syncthreads();
+    }
+    for (int m = tid; m < n2; m += blockDim.x)
+        if (state[m] >= 2) sel[cum[cur][m] - 1] = m;
+    // slots ordered by label id (slots without weight last), for the expected count of a label
+    for (int size = 2; size <= n2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int t = tid; t < n2 / 2; t += blockDim.x) {
+                const int lo = 2 * t - (t & (stride - 1));
+                const int hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const uint64_t a = byid[lo], b = byid[hi];
+                if ((a > b) == up) { byid[lo] = b; byid[hi] = a; }
+            }
+            __syncthreads();
+        }
+    }
+    const double unif = static_cast<double>(n - k) / static_cast<double>(L);
+    for (int j = tid; j < n; j += blockDim.x) {
+        int64_t lab;
+        if (j < k) lab = ids[sel[j]];
+        else lab = static_cast<int64_t>(__umul64hi(fmix64(qstate + kDrawMul * static_cast<uint64_t>(j + 1)), static_cast<uint64_t>(L)));
+        double c = 0.0;
+        if (k > 0) {
+            const uint64_t key = static_cast<uint64_t>(lab) << 32;
+            int lo = 0, hi = n2;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (byid[mid] < key) lo = mid + 1; else hi = mid;
+            }
+            for (int p = lo; p < n2 && (byid[p] >> 32) == static_cast<uint64_t>(lab); ++p)
+                c += pi[static_cast<uint32_t>(byid[p])];                   // in slot order
+        }
+        neg[i * n + j] = static_cast<int32_t>(lab);
+        logq[i * n + j] = static_cast<float>(log(c + unif));
+    }
+}
+
 }  // namespace xc
 
 extern "C" int xc_sample_negatives(const int32_t* shortlist, int64_t B, int k_h, int k_r, int64_t L,
@@ -261,6 +415,22 @@ extern "C" int xc_sample_negatives_mixture(const int32_t* shortlist, const float
     while (n2 < M) n2 <<= 1;
     hipStream_t st = static_cast<hipStream_t>(stream);
     XC_LAUNCH(K_SAMPLE, st, (sample_mixture_kernel<<<dim3(static_cast<unsigned>(B)), kSampleThreads, 0, st>>>(
+        shortlist, scores, M, k_h, k_r, L, seed, n2, neg, logq)));
+    XC_HIP_CHECK(hipGetLastError());
+    return XC_OK;
+}
+
+extern "C" int xc_sample_negatives_pps(const int32_t* shortlist, const float* scores, int64_t B, int M,
+                                       int k_h, int k_r, int64_t L, uint64_t seed, int32_t* neg,
+                                       float* logq, void* stream) {
+    using namespace xc;
+    if (B < 1 || B > 0x7fffffffLL || M < 1 || M > XC_MAX_K_SAMPLE) return XC_ESHAPE;
+    if (k_h < 0 || k_h > XC_MAX_K_SAMPLE || k_r < 0 || k_h + k_r < 1 || L < 1 || L > 0x7fffffffLL) return XC_ESHAPE;
+    if (!shortlist || !scores || !neg || !logq) return XC_EINVAL;
+    int n2 = 2;
+    while (n2 < M) n2 <<= 1;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    XC_LAUNCH(K_SAMPLE, st, (sample_pps_kernel<<<dim3(static_cast<unsigned>(B)), kSampleThreads, 0, st>>>(
         shortlist, scores, M, k_h, k_r, L, seed, n2, neg, logq)));
     XC_HIP_CHECK(hipGetLastError());
     return XC_OK;

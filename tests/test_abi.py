@@ -63,6 +63,8 @@ def test_host_side_argument_checks(lib):
     assert b.xc_sample_negatives_mixture(None, None, 4, 0, 8, 16, 100, 1, None, None, None) == -2      # M < 1
     assert b.xc_sample_negatives_mixture(None, None, 4, 2000, 8, 16, 100, 1, None, None, None) == -2   # M too wide
     assert b.xc_sample_negatives_mixture(None, None, 4, 12, 8, 16, 100, 1, None, None, None) == -1     # null pointers
+    assert b.xc_sample_negatives_pps(None, None, 4, 0, 8, 16, 100, 1, None, None, None) == -2          # M < 1
+    assert b.xc_sample_negatives_pps(None, None, 4, 12, 8, 16, 100, 1, None, None, None) == -1         # null pointers
     assert b.xc_mfma_probe(None, 10, 1, None, None) == -1
     assert b.xc_copy_probe(None, None, 64, None) == -1
     assert b.xc_mine_negatives(None, None, 1, 100, 64, 8, 1, None, None, None, 0, None) == -1

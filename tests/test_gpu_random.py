@@ -115,3 +115,24 @@ def test_random_mixture_sampling(seed):
         neg_o, logq_o = orc.sample_negatives_mixture(sl, sc, B, M, k_h, k_r, L, s)
         assert (neg.cpu().numpy() == neg_o).all()
         assert np.allclose(logq.cpu().numpy(), logq_o, rtol=2e-7, atol=0)
+
+
+@pytest.mark.parametrize("seed", [501, 502])
+def test_random_sampling_without_replacement(seed):
+    import paper_2409_20156_amd as xc
+    rng = np.random.default_rng(seed)
+    for it in range(8):
+        B = int(rng.integers(1, 30))
+        L = int(rng.choice([10, 200, 4096, 131072, 8_600_000, 120_000_000]))
+        M = int(rng.integers(1, 1025))
+        k_h = int(rng.integers(0, 300))
+        k_r = int(rng.integers(0 if k_h else 1, 400))
+        s = int(rng.integers(0, 2 ** 63)) * 2 + int(rng.integers(0, 2))
+        sl = np.stack([rng.choice(L, size=M, replace=M > L) for _ in range(B)]).astype(np.int32)
+        sl[rng.random(sl.shape) < rng.choice([0.0, 0.2])] = -1
+        sc = (rng.standard_normal((B, M)) * float(rng.choice([0.2, 1.0, 8.0, 40.0]))).astype(np.float32)
+        print("pps", seed, it, B, L, M, k_h, k_r, s, flush=True)
+        neg, logq = xc.sample_negatives_pps(torch.tensor(sl, device=DEV), torch.tensor(sc, device=DEV), k_h, k_r, L, s)
+        neg_o, logq_o = orc.sample_negatives_pps(sl, sc, B, M, k_h, k_r, L, s)
+        assert (neg.cpu().numpy() == neg_o).all()
+        assert np.allclose(logq.cpu().numpy(), logq_o, rtol=2e-7, atol=0)

@@ -143,3 +143,82 @@ def test_mixture_pipeline_from_mined_scores():
     ref = orc.xc_step(Z64, W64, pos, neg_o, logq_o, 0.3, storage="f32")
     assert abs(float(out["loss"].item()) - ref["loss"]) <= TOL["f32"] * abs(ref["loss"])
     check_rows_close(out["dZ"].cpu().numpy(), ref["dZ"], TOL["f32"], "dZ")
+
+
+# ------------------------------------- hard negatives sampled without replacement from a wider shortlist ----
+def _gpu_pps(sl, sc, k_h, k_r, L, seed):
+    import paper_2409_20156_amd as xc
+    neg, logq = xc.sample_negatives_pps(torch.tensor(sl, dtype=torch.int32, device="cuda:0"),
+                                        torch.tensor(sc, dtype=torch.float32, device="cuda:0"),
+                                        k_h, k_r, L, seed)
+    torch.cuda.synchronize()
+    return neg.cpu().numpy(), logq.cpu().numpy()
+
+
+@pytest.mark.parametrize("B,M,k_h,k_r,L,seed,scale", [
+    (32, 24, 8, 16, 4096, 20240930, 1.0),        # Tiny-like, shortlist three times as wide as k_h
+    (9, 200, 50, 200, 131072, 5, 0.2),           # scores of the size the random data gives: no slot certain
+    (4, 1024, 64, 256, 1300000, 2 ** 63 + 1, 8.0),   # widest shortlist, saturated sigmoids: many certain slots
+    (3, 1, 5, 0, 10, 3, 1.0),                    # one slot for five places: the rest uniform
+    (5, 37, 0, 50, 120000000, 8, 1.0),           # no importance part
+    (6, 16, 700, 300, 1000, 9, 40.0),            # more places than slots and than threads, clamped scores
+    (7, 64, 63, 5, 5000, 11, 3.0),               # all but one slot taken: rounds of certain slots
+    (8, 100, 100, 0, 120000000, 12, 1.0),        # as many places as slots: all certain
+])
+def test_pps_sample_bit_exact(B, M, k_h, k_r, L, seed, scale):
+    print("case", B, M, k_h, k_r, L, seed, flush=True)
+    rng = np.random.default_rng(B * 137 + M)
+    sl = np.stack([rng.choice(L, size=M, replace=M > L) for _ in range(B)]).astype(np.int32)
+    sc = (rng.standard_normal((B, M)) * scale).astype(np.float32)
+    neg, logq = _gpu_pps(sl, sc, k_h, k_r, L, seed)
+    neg_o, logq_o = orc.sample_negatives_pps(sl, sc, B, M, k_h, k_r, L, seed)
+    assert (neg == neg_o).all()
+    assert np.allclose(logq, logq_o, rtol=2e-7, atol=0)
+    for i in range(B):                             # without replacement: distinct shortlist slots (distinct ids here)
+        k = min(k_h, M)
+        if M <= L:
+            assert len(set(neg[i, :k].tolist())) == k
+
+
+def test_pps_sample_degenerate_rows():
+    B, M, k_h, k_r, L = 6, 20, 7, 13, 3000
+    rng = np.random.default_rng(4)
+    sl = np.stack([rng.choice(L, size=M, replace=False) for _ in range(B)]).astype(np.int32)
+    sc = rng.standard_normal((B, M)).astype(np.float32)
+    sl[0, :] = -1                                   # no valid slot: uniform draws only
+    sl[1, 5] = sl[1, 2]; sl[1, 9] = sl[1, 2]        # one label in three slots
+    sl[2, ::2] = L + 5                              # out-of-range ids are padding
+    sc[3, :] = np.float32("nan"); sc[3, 4] = 0.25   # a single usable slot
+    sc[4, 0] = np.float32("inf"); sc[4, 1] = -np.float32("inf")
+    sc[5, :] = -30.0                                # all weights at the floor of the clamp
+    neg, logq = _gpu_pps(sl, sc, k_h, k_r, L, 99)
+    neg_o, logq_o = orc.sample_negatives_pps(sl, sc, B, M, k_h, k_r, L, 99)
+    assert (neg == neg_o).all()
+    assert np.allclose(logq, logq_o, rtol=2e-7, atol=0)
+    assert neg[3, 0] == sl[3, 4]
+
+
+def test_pps_pipeline_from_mined_scores():
+    """Mine a shortlist wider than k_h with scores, sample the hard negatives from it without replacement,
+    take one step: the whole chain on the GPU against the oracle fed with the oracle's own mining."""
+    import paper_2409_20156_amd as xc
+    from paper_2409_20156_amd import synth
+    from tests.parity import TOL, check_rows_close, f64
+    dev = "cuda:0"
+    B, L, d, M, k_h, k_r = 24, 3000, 64, 32, 8, 40
+    W = synth.make_matrix(21, synth.TAG_W, L, d, torch.float32, dev)
+    Z = synth.make_matrix(21, synth.TAG_Z, B, d, torch.float32, dev) * 4.0       # scores of order one
+    pos = synth.zipf_positives(21, B, L, 1.0, "uniform:1:2", 2)
+    Z64, W64 = f64(Z), f64(W)
+    sl_o, sc_o = orc.mine_negatives(Z64, W64, M)
+    sc_o32 = sc_o.astype(np.float32)
+    sl_g, sc_g = xc.mine_negatives(Z, W, M, want_scores=True)
+    assert (sl_g.cpu().numpy() == sl_o).all()
+    # (both samplers get the oracle's scores rounded to float32: a last-bit difference in a score cannot move an id)
+    neg_g, logq_g = xc.sample_negatives_pps(sl_g, torch.tensor(sc_o32, device=dev), k_h, k_r, L, 17)
+    neg_o, logq_o = orc.sample_negatives_pps(sl_o, sc_o32, B, M, k_h, k_r, L, 17)
+    assert (neg_g.cpu().numpy() == neg_o).all()
+    out = xc.xc_step(Z, W.clone(), torch.tensor(pos, device=dev), neg_g, logq_g, 0.3)
+    ref = orc.xc_step(Z64, W64, pos, neg_o, logq_o, 0.3, storage="f32")
+    assert abs(float(out["loss"].item()) - ref["loss"]) <= TOL["f32"] * abs(ref["loss"])
+    check_rows_close(out["dZ"].cpu().numpy(), ref["dZ"], TOL["f32"], "dZ")
