@@ -647,6 +647,13 @@ static bool force_general_kernel() {
     return v;
 }
 
+// The lane number, computed where it is asked for (the compiler can neither hoist nor keep it).
+__device__ __forceinline__ uint32_t lane_now() {
+    uint32_t l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmem_at_most() {   // until at most N vector memory operations are outstanding
     __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | 0x0070 | 0x0f00);
@@ -808,29 +815,39 @@ void mine_rows_kernel(const MineArgs a) {
         publish(0);
 
         // ---- threshold filter of one N block (the lane owns query column (lane & 31) of it) of the tile that
-        // starts at label l0
-        auto filter = [&](auto ntc, int64_t l0) {
+        // starts at label l0: the block's largest score per lane, and, where some lane's reaches its threshold,
+        // the scores one by one
+        auto block_max = [&](auto ntc) {
             constexpr int nt = decltype(ntc)::value;
-            const float t = tau[nt];
             float mx = acc[0][nt][0];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[mt][nt][i]);
-            if (__builtin_expect(__ballot(mx >= t) != 0ull, 0)) {
-                const int qloc = wn * 64 + nt * 32 + (lane & 31);
-                uint64_t* mine = my_lists + static_cast<size_t>(qloc * 4 + wm * 2 + half) * kSubCap;
-                const int32_t lrow = static_cast<int32_t>(l0) + wm * 64 + 4 * half;
+            return mx;
+        };
+        auto push_block = [&](auto ntc, int64_t l0, float mx) {
+            constexpr int nt = decltype(ntc)::value;
+            const float t = tau[nt];
+            if (__ballot(mx >= t) != 0ull) {
+                // Everything a push needs is formed here from the lane number, read afresh, and from wave-uniform
+                // values: a per-lane pointer or row number kept in a register over the main loop would be
+                // spilled there, and its reload would wait for every stage load in flight.
                 const int32_t lmax = static_cast<int32_t>(a.L);
+                const int32_t lbase = static_cast<int32_t>(l0) + wm * 64;
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const float v = acc[mt][nt][i];
-                        const int32_t lab = lrow + mt * 32 + 8 * (i >> 2) + (i & 3);
-                        const bool hit = v >= t && lab < lmax;      // rows past the end repeat the last row
-                        if (__builtin_expect(__ballot(hit) != 0ull, 0)) {
-                            if (hit) { mine[cnt[nt]] = make_key(v + 0.0f /* -0 -> +0 */, lab); ++cnt[nt]; }
+                        if (__builtin_expect(__ballot(v >= t) != 0ull, 0)) {
+                            const uint32_t l = lane_now();
+                            const int32_t lab = lbase + 4 * static_cast<int32_t>(l >> 5) + mt * 32 + 8 * (i >> 2) + (i & 3);
+                            if (v >= t && lab < lmax) {             // rows past the end repeat the last row
+                                const uint32_t sub = static_cast<uint32_t>(((wn * 64 + nt * 32) * 4 + wm * 2)) + (l & 31u) * 4u + (l >> 5);
+                                my_lists[sub * kSubCap + static_cast<uint32_t>(cnt[nt])] = make_key(v + 0.0f /* -0 -> +0 */, lab);
+                                ++cnt[nt];
+                            }
                         }
                     }
             }
@@ -897,9 +914,14 @@ void mine_rows_kernel(const MineArgs a) {
                 }
                 ++g;
             }
-            filter(IC<0>{}, l0);
-            filter(IC<1>{}, l0);
-            cut_lists();
+            // one test per tile on the usual way: does any lane see a score at its threshold, or a list to cut?
+            const float mx0 = block_max(IC<0>{}), mx1 = block_max(IC<1>{});
+            const bool look = mx0 >= tau[0] || mx1 >= tau[1] || cnt[0] > kSubFull || cnt[1] > kSubFull;
+            if (__builtin_expect(__ballot(look) != 0ull, 0)) {
+                push_block(IC<0>{}, l0, mx0);
+                push_block(IC<1>{}, l0, mx1);
+                cut_lists();
+            }
         }
 
         // ---- close the slice: the four lists of a query go to its global list
