@@ -10,6 +10,11 @@ later ones started from the thresholds of the one before, same result), or, for
 the workloads defined as "one mining pass plus N steps" (c3, c4, c5), once per N
 steps.  So `value` always contains the mining the workload defines.
 
+`--steps K` times exactly K steps of that schedule from its start (so one search
+and K steps when K is below the search period); the share of search per step
+then differs from the workload's, and the whole scripted run is timed too and
+reported beside it (`scripted_run`).
+
 The default workload is the largest configuration of the baseline file that fits
 one GPU: c5 (L = 120 M labels, d = 256, bf16, about 61 GB of classifier rows,
 B = 4096, one search over 16 384 queries plus 100 steps).  The smaller
@@ -43,7 +48,10 @@ HEADLINE = "c5"
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0, help="timed steps (default: the workload's scripted run)")
+    ap.add_argument("--steps", type=int, default=0,
+                    help="timed steps (default: the workload's scripted run, 100 for c5).  With another number the "
+                         "timed region is that many steps of the schedule from its start, one search included, and "
+                         "the whole scripted run is timed as well and reported under `scripted_run`")
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=HEADLINE, help="tiny, c2, c3, c4 or c5")
     ap.add_argument("--also", default=None,
@@ -137,8 +145,8 @@ class Job:
         return b
 
 
-def cpu_baseline(wl, pool, steps):
-    """The oracle as it stands on a bounded sample of about 10-30 s of CPU work, scaled to the scripted run.
+def cpu_baseline(wl, pool, steps_per_search):
+    """The oracle as it stands on a bounded sample of about 10-30 s of CPU work, scaled to the timed region (one search per `steps_per_search` steps).
 
     Search: `nq` queries against the first `Ls` labels (all of them where the float64 matrix stays below
     about 4 GB, else a prefix whose rows are generated on the fly), scaled linearly to pool x L.
@@ -181,7 +189,7 @@ def cpu_baseline(wl, pool, steps):
         t0 = time.perf_counter()
         orc.xc_step(Z[:nb], rows, pos_c, neg_c, logq, wl.lr, storage=wl.dtype)
         t_step_q = (t_sample + time.perf_counter() - t0) / nb
-    period = wl.refresh if wl.refresh else wl.steps
+    period = steps_per_search                                          # as in the timed region of this run
     per_query = t_step_q + t_mine_pair * wl.L * pool / (period * wl.B)
     try:
         import threadpoolctl
@@ -190,7 +198,7 @@ def cpu_baseline(wl, pool, steps):
         cores = os.cpu_count() or 1
     return {"value": 1.0 / per_query, "unit": "queries/s", "cores": cores, "kind": "oracle",
             "sample": "search: %d queries x the first %d of %d labels, scaled linearly to the pool of %d queries x all "
-                      "labels, one search per %d steps (extrapolated); sampling + step: %d queries of a batch%s, "
+                      "labels, one search per %g steps as in this run's timed region (extrapolated); sampling + step: %d queries of a batch%s, "
                       "scaled to B=%d; numpy float64 oracle, BLAS threads = cores"
                       % (nq, Ls, wl.L, pool, period, nb,
                          "" if Ls == wl.L else " on the renumbered sub-problem holding the rows their pairs use", wl.B),
@@ -311,6 +319,19 @@ def run_workload(args, name, steps=0, warmup=None, structured=False, profile_pas
                            "frac_of_8TBs": step_bytes / (step_us * 1e-6) / 1e9 / PEAK_HBM_GBS}
     res["roofline"] = roofline
     res["kernels_us"] = {n: round(k["avg_us"], 2) for n, k in kernels.items()}
+    if K != wl.steps:
+        # the timed region above is the K steps that were asked for, with the searches the schedule puts there
+        # (one at its start): a different share of search per step than the workload defines.  The workload's
+        # whole scripted run, timed the same way, beside it:
+        job.restart()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(wl.steps):
+            job.step()
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        res["scripted_run"] = {"steps": wl.steps, "value": wl.B * wl.steps / el, "unit": "queries/s",
+                               "ms_per_step": el * 1e3 / wl.steps, "searches": dict(job.searches)}
     del job
     torch.cuda.empty_cache()
     return wl, pool, res
@@ -352,11 +373,11 @@ def main():
         "roofline": head["roofline"],
         "kernels_us": head["kernels_us"],
     }
-    for k in ("mine_pairs_per_s", "mine_ms_per_search", "rows_per_step", "step_hbm"):
+    for k in ("mine_pairs_per_s", "mine_ms_per_search", "rows_per_step", "step_hbm", "scripted_run"):
         if k in head:
             result[k] = head[k]
 
-    default_run = args.workload == HEADLINE and not args.steps and not args.pool and not args.structured
+    default_run = args.workload == HEADLINE and not args.pool and not args.structured
     if default_run and not args.no_structured_line and not args.no_profile_pass:
         # the structured variant of the same workload (queries pulled towards a positive), beside the i.i.d. run
         _, _, st = run_workload(args, args.workload, structured=True, profile_pass=True)
@@ -398,7 +419,8 @@ def main():
     result["achievable"] = achievable
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, pool, head["steps"])
+        n_search = sum(head["searches_in_timed_region"].values())
+        result["cpu_baseline"] = cpu_baseline(wl, pool, head["steps"] / max(1, n_search))
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result))
