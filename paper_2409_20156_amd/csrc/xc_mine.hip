@@ -618,28 +618,32 @@ void mine_tile_kernel(const MineArgs a) {
 // (NK = row bytes / 128 = 1..4), where a wave's share of the query tile fits its registers.
 //   * The query tile never passes through LDS: wave (wm, wn) keeps the MFMA B operands of its 64
 //     queries for the whole row in registers (NK * 32 of them), loaded once per work item.
-//   * Only W is streamed: a label tile is 128 labels, staged 128 bytes of each row at a time
-//     (16 KiB) through a ring of kRing stages in LDS, filled kRing - 1 stages ahead by direct
-//     global->LDS loads, issued by one wave per SIMD in turn.  Half the staged bytes per
-//     flop of the general kernel, and 2 operand reads from LDS per 4 MFMAs instead of 6 per 8.
-//   * A wave computes 64 labels x 64 queries (2 x 2 MFMA blocks).  A lane owns two query columns
-//     and the thresholds of exactly those, which it keeps in registers.  A passing score goes
-//     straight to a candidate list that belongs to the lane alone (4 owners per query: 2 waves
-//     x 2 lane halves, 256 keys each, in the workgroup's part of the workspace), at a position
-//     the lane counts itself: no atomics, no LDS, no barrier on the path.
+//   * Only W is streamed: a label tile is 64 WM labels, staged 128 bytes of each row at a time
+//     through a ring of kRing stages in LDS, filled kRing - 1 stages ahead by direct
+//     global->LDS loads, issued by one wave per SIMD in turn.  2 operand reads from LDS per 4
+//     MFMAs instead of 6 per 8.
+//   * A wave computes 64 labels x 64 queries (2 x 2 MFMA blocks); the 8 waves are laid out WM
+//     along the labels x 8 / WM along the queries.  WM = 2: 128 labels x 256 queries per tile,
+//     half the bytes staged per flop of the general kernel.  WM = 1: 64 labels x 512 queries
+//     (two adjacent 256-query tiles form one work item), a quarter; for pools that fill it.
+//   * A lane owns two query columns and the thresholds of exactly those, which it keeps in
+//     registers.  A passing score goes straight to a candidate list that belongs to the lane
+//     alone (2 WM owners per query: WM waves x 2 lane halves, 256 keys each, in the workgroup's
+//     part of the workspace), at a position the lane counts itself: no atomics, no LDS, no
+//     barrier on the path.
 //   * A lane's list that could overflow in the next tile is cut to its best k by the lane's wave
 //     (every label of the overall best k that is in this list is among the list's own best k),
 //     and the lane's threshold rises to the k-th of them.  Nothing of that involves other waves.
-//   * At the end of the slice the four lists of a query are appended to its global list, cut to
-//     the best k first if they hold more than a slice may append.
+//   * At the end of the slice the lists of a query are appended to its global list, cut to
+//     the best k of them all first if they hold more than a slice may append.
 // ---------------------------------------------------------------------------
-constexpr int kRowTile = 128;       // labels per tile of the row kernel
-constexpr int kRing = 8;            // stages of 16 KiB in LDS
-constexpr int kRowStage = kRowTile * kStageBytes;
+constexpr int kRing = 8;            // stages in LDS (8 or 16 KiB each)
 static_assert(kRing >= 4 && (kRing & (kRing - 1)) == 0, "stage slots are indexed modulo a power of two, and the two halves of the workgroup fill them in turn");
 constexpr int kSubCap = kCandCap / 4;            // keys of a lane's own list
 constexpr int kSubFull = kSubCap - 32;           // above this a tile could overflow it (a lane adds <= 32 per column)
-constexpr size_t kRowsLds = static_cast<size_t>(kRing) * kRowStage + kBN * 4 * sizeof(int) + kMineWaves * 256 * sizeof(int);
+constexpr size_t rows_lds_bytes(int wm) {     // ring, list fills at the end of a slice, select histograms
+    return static_cast<size_t>(kRing) * wm * 64 * kStageBytes + kBN * 4 * sizeof(int) + kMineWaves * 256 * sizeof(int);
+}
 
 // XC_MINE_GENERAL=1 in the environment sends every shape through the general tile kernel (for A/B timing)
 static bool force_general_kernel() {
@@ -661,21 +665,27 @@ __device__ __forceinline__ void wait_vmem_at_most() {   // until at most N vecto
 
 // Stage fill of the last, ragged label tile: per-lane addresses, rows past the end repeat the last row.
 __device__ __noinline__ void issue_stage_ragged(const unsigned char* W, int64_t L, int64_t row, int row_bytes, int kbyte,
-                                                uint32_t dcol0, uint32_t dcol1, uint32_t dst) {
+                                                uint32_t dcol0, uint32_t dcol1, uint32_t dst, int n_instr) {
 #pragma unroll 1
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < n_instr; ++t) {
         int64_t r = row + 8 * t;
         r = r < L ? r : L - 1;
         lds_dma16(W + r * row_bytes + kbyte + ((t & 1) ? dcol1 : dcol0), __builtin_amdgcn_readfirstlane(dst + t * 1024));
     }
 }
 
-template <int NK>
+template <int NK, int WM>
 __global__ __launch_bounds__(kMineThreads, 1)
 void mine_rows_kernel(const MineArgs a) {
+    constexpr int kRowTile = 64 * WM;                   // labels per tile
+    constexpr int kRowStage = kRowTile * kStageBytes;   // bytes of a stage
+    constexpr int kQN = (kMineWaves / WM) * 64;         // queries per work item
+    constexpr int kOwn = 2 * WM;                        // lists per query (kOwn * kQN = 4 kBN)
+    constexpr int kQCap = kOwn * kSubCap;               // keys of a query's lists together
+    constexpr int kLd = 2 * WM;                         // load instructions of a wave per stage it brings in
     extern __shared__ __align__(16) unsigned char smem[];
     if (a.cond != nullptr && a.cond[0] == 0) return;          // uniform: a repeat that is not needed
-    int* cnt4 = reinterpret_cast<int*>(smem + kRing * kRowStage);            // [kBN][4] list fills at the end of a slice
+    int* cnt4 = reinterpret_cast<int*>(smem + kRing * kRowStage);            // [kQN][kOwn] list fills at the end of a slice
     int* hist = cnt4 + kBN * 4;                                             // [kMineWaves][256]
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) unsigned char*)smem));
@@ -683,11 +693,13 @@ void mine_rows_kernel(const MineArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave & 1;          // which 64-label half of the tile
-    const int wn = wave >> 1;         // which 64-query quarter
+    const int wm = wave % WM;         // which 64 labels of the tile
+    const int wn = wave / WM;         // which 64 queries of the work item
     const int half = lane >> 5;
     uint64_t* my_lists = a.lists + static_cast<size_t>(blockIdx.x) * kBN * kCandCap;
     constexpr int row_bytes = NK * kStageBytes;
+    // a query takes part if it exists and, in the repeat of a warm search, if its 256-query tile needs it
+    auto live = [&](int64_t q) { return q < a.Zq && (a.cond == nullptr || a.cond[1 + q / kBN] != 0); };
 
     int item, item_step, item_end;
     int slice_fixed = -1;
@@ -707,8 +719,8 @@ void mine_rows_kernel(const MineArgs a) {
     // stage fill.  Waves w and w + 4 share a SIMD.  A stage is brought in by four waves, one per SIMD, while
     // their SIMD-mates start on the MFMAs at once (a wave that issues loads queues at the texture unit behind
     // the other waves' loads; if all eight issued, every SIMD's matrix pipe would idle meanwhile); waves 0..3
-    // take the even stages, waves 4..7 the odd ones.  Wave w brings in rows 32 (w & 3) .. + 31 of the stage
-    // with four instructions of 8 rows; lane i -> row i / 8, position i % 8, source chunk = position ^ swizzle(row)
+    // take the even stages, waves 4..7 the odd ones.  Wave w brings in rows 8 kLd (w & 3) .. + 8 kLd - 1 of the stage
+    // with kLd instructions of 8 rows; lane i -> row i / 8, position i % 8, source chunk = position ^ swizzle(row)
     const int drow = lane >> 3;
     const int wq = wave & 3;
     const int my_parity = wave >> 2;
@@ -716,11 +728,16 @@ void mine_rows_kernel(const MineArgs a) {
                               static_cast<uint32_t>(((lane & 7) ^ ((lane >> 4) + 4)) * 16)};
     const uint32_t voff[2] = {static_cast<uint32_t>(drow * row_bytes) + dcol[0],
                               static_cast<uint32_t>((drow + 8) * row_bytes) + dcol[1]};
-    const uint32_t dma_dst = lds_base + wq * 4 * 1024;
+    const uint32_t dma_dst = lds_base + wq * kLd * 1024;
 
     for (; item < item_end; item += item_step) {
         const int64_t qtile = a.Qx > 0 ? item : item / a.S;
-        if (a.cond != nullptr && a.cond[1 + qtile] == 0) continue;
+        const int64_t q0 = qtile * kQN;
+        if (a.cond != nullptr) {                             // uniform: every 256-query tile of the item came out complete
+            bool any = false;
+            for (int64_t qt = q0 / kBN; qt < (q0 + kQN) / kBN && qt * kBN < a.Zq; ++qt) any = any || a.cond[1 + qt] != 0;
+            if (!any) continue;
+        }
         const int slice = a.Qx > 0 ? slice_fixed : static_cast<int>(item % a.S);
         const int64_t t_begin = a.tile_lo + static_cast<int64_t>(slice) * a.tiles_per_slice;
         int64_t lab_begin, lab_end;
@@ -734,7 +751,6 @@ void mine_rows_kernel(const MineArgs a) {
         }
         const int n_tiles = static_cast<int>((lab_end - lab_begin + kRowTile - 1) / kRowTile);
         const int n_stages = n_tiles * NK;
-        const int64_t q0 = qtile * kBN;
 
         // ---- this wave's queries: B operands for the whole row, thresholds of the lane's two columns
         uint4 zf[NK * 4][2];
@@ -744,7 +760,7 @@ void mine_rows_kernel(const MineArgs a) {
         for (int nt = 0; nt < 2; ++nt) {
             const int64_t q = q0 + wn * 64 + nt * 32 + (lane & 31);
             const int64_t qc = q < a.Zq ? q : a.Zq - 1;
-            tau[nt] = q < a.Zq ? ordered_to_float(a.tau_g[q]) : INFINITY;
+            tau[nt] = live(q) ? ordered_to_float(a.tau_g[q]) : INFINITY;
             const unsigned char* zr = a.Z + qc * row_bytes + half * 16;
 #pragma unroll
             for (int ks = 0; ks < NK * 4; ++ks) zf[ks][nt] = *reinterpret_cast<const uint4*>(zr + ks * 32);
@@ -757,7 +773,7 @@ void mine_rows_kernel(const MineArgs a) {
         // ---- the load stream: stage g = (tile g / NK, bytes 128 (g % NK) .. of the rows) goes to slot g % kRing
         int ld_stage = 0, ld_kb = 0, ld_tile = 0;
         uint32_t ld_dst = dma_dst;
-        const unsigned char* ld_w = a.W + (lab_begin + wq * 32) * row_bytes;        // this wave's rows of the tile being loaded
+        const unsigned char* ld_w = a.W + (lab_begin + wq * 8 * kLd) * row_bytes;   // this wave's rows of the tile being loaded
         const int full_tiles = static_cast<int>((a.L - lab_begin) / kRowTile < n_tiles ? (a.L - lab_begin) / kRowTile : n_tiles);
         auto issue_stage = [&]() {
             if ((ld_stage & 1) != my_parity) {
@@ -770,27 +786,29 @@ void mine_rows_kernel(const MineArgs a) {
                     static_cast<uint64_t>(static_cast<uint32_t>(
                         __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64))));
                 const unsigned char* sp = reinterpret_cast<const unsigned char*>(sb);
-                const unsigned char* sp2 = sp + 16 * row_bytes;
                 lds_dma16_sbase<0>(sp, voff[0], ld_dst);
                 lds_dma16_sbase<1024>(sp, voff[1], ld_dst);
-                lds_dma16_sbase<2048>(sp2, voff[0], ld_dst);
-                lds_dma16_sbase<3072>(sp2, voff[1], ld_dst);
+                if (WM == 2) {
+                    const unsigned char* sp2 = sp + 16 * row_bytes;
+                    lds_dma16_sbase<2048>(sp2, voff[0], ld_dst);
+                    lds_dma16_sbase<3072>(sp2, voff[1], ld_dst);
+                }
             } else {
                 // the last tile of the label range: rows past the end repeat the last row (dropped by the filter)
-                issue_stage_ragged(a.W, a.L, lab_begin + static_cast<int64_t>(ld_tile) * kRowTile + wq * 32 + drow,
-                                   row_bytes, ld_kb * kStageBytes, dcol[0], dcol[1], ld_dst);
+                issue_stage_ragged(a.W, a.L, lab_begin + static_cast<int64_t>(ld_tile) * kRowTile + wq * 8 * kLd + drow,
+                                   row_bytes, ld_kb * kStageBytes, dcol[0], dcol[1], ld_dst, kLd);
             }
             ++ld_stage;
             ld_dst += kRowStage;
             if ((ld_stage & (kRing - 1)) == 0) ld_dst = dma_dst;
             if (++ld_kb == NK) { ld_kb = 0; ++ld_tile; ld_w += kRowTile * row_bytes; }
         };
-        // This wave's part of stage g (if it has one) is complete once at most 4 * (its stages issued after g)
+        // This wave's part of stage g (if it has one) is complete once at most kLd * (its stages issued after g)
         // loads are outstanding: of the kRing - 2 stages issued after g in the steady state half are this
         // wave's, whichever half g belongs to.  Stores of the filter only make the wait stricter (loads complete
         // in order among themselves).  Near the end of the work item everything is awaited.
         auto wait_stage = [&](int g) {
-            if (ld_stage - 1 - g >= kRing - 2) wait_vmem_at_most<4 * ((kRing - 2) / 2)>();
+            if (ld_stage - 1 - g >= kRing - 2) wait_vmem_at_most<kLd * ((kRing - 2) / 2)>();
             else wait_all_vmem();
         };
 
@@ -844,7 +862,7 @@ void mine_rows_kernel(const MineArgs a) {
                             const uint32_t l = lane_now();
                             const int32_t lab = lbase + 4 * static_cast<int32_t>(l >> 5) + mt * 32 + 8 * (i >> 2) + (i & 3);
                             if (v >= t && lab < lmax) {             // rows past the end repeat the last row
-                                const uint32_t sub = static_cast<uint32_t>(((wn * 64 + nt * 32) * 4 + wm * 2)) + (l & 31u) * 4u + (l >> 5);
+                                const uint32_t sub = static_cast<uint32_t>(((wn * 64 + nt * 32) * kOwn + wm * 2)) + (l & 31u) * kOwn + (l >> 5);
                                 my_lists[sub * kSubCap + static_cast<uint32_t>(cnt[nt])] = make_key(v + 0.0f /* -0 -> +0 */, lab);
                                 ++cnt[nt];
                             }
@@ -865,7 +883,7 @@ void mine_rows_kernel(const MineArgs a) {
                         todo &= todo - 1;
                         const int qsel = wn * 64 + nt * 32 + (src & 31);
                         const int nsel = __shfl(cnt[nt], src, kWave);
-                        uint64_t* lsel = my_lists + static_cast<size_t>(qsel * 4 + wm * 2 + (src >> 5)) * kSubCap;
+                        uint64_t* lsel = my_lists + static_cast<size_t>(qsel * kOwn + wm * 2 + (src >> 5)) * kSubCap;
                         const float tk = wave_select_k<kSubCap / kWave>(
                             lsel, [lsel](int idx) { return lsel[idx]; }, nsel, a.k, hist + wave * 256);
                         if (lane == src) { cnt[nt] = a.k; tau[nt] = fmaxf(tau[nt], tk); }
@@ -924,37 +942,45 @@ void mine_rows_kernel(const MineArgs a) {
             }
         }
 
-        // ---- close the slice: the four lists of a query go to its global list
+        // ---- close the slice: the lists of a query go to its global list
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) cnt4[(wn * 64 + nt * 32 + (lane & 31)) * 4 + wm * 2 + half] = cnt[nt];
+        for (int nt = 0; nt < 2; ++nt) cnt4[(wn * 64 + nt * 32 + (lane & 31)) * kOwn + wm * 2 + half] = cnt[nt];
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         __syncthreads();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        {
-            const int ql = wave * 32 + (lane & 31);          // lanes l and l + 32 look after query 32 wave + l
-            const bool qok = (q0 + ql) < a.Zq;
-            int c[4];
+#pragma unroll 1
+        for (int qr = 0; qr < kQN; qr += kMineWaves * 32) {
+            const int qw = qr + wave * 32;                   // lanes l and l + 32 look after query qw + l
+            const int ql = qw + (lane & 31);
+            const bool qok = live(q0 + ql);
+            int c[kOwn];
             int n = 0;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) { c[s] = qok ? cnt4[ql * 4 + s] : 0; n += c[s]; }
-            uint64_t* qlist = my_lists + static_cast<size_t>(ql) * kCandCap;
+            for (int s = 0; s < kOwn; ++s) { c[s] = qok ? cnt4[ql * kOwn + s] : 0; n += c[s]; }
+            uint64_t* qlist = my_lists + static_cast<size_t>(ql) * kQCap;
             uint64_t todo = __ballot(lane < 32 && n > a.append_max);
-            while (todo) {                                   // more than a slice may append: the best k of all four
+            while (todo) {                                   // more than a slice may append: the best k of them all
                 const int src = __ffsll(static_cast<long long>(todo)) - 1;
                 todo &= todo - 1;
-                int cs[4];
+                int cs[kOwn];
+                int ntot = 0;
 #pragma unroll
-                for (int s = 0; s < 4; ++s) cs[s] = __shfl(c[s], src, kWave);
-                uint64_t* lsel = my_lists + static_cast<size_t>(wave * 32 + src) * kCandCap;
+                for (int s = 0; s < kOwn; ++s) { cs[s] = __shfl(c[s], src, kWave); ntot += cs[s]; }
+                uint64_t* lsel = my_lists + static_cast<size_t>(qw + src) * kQCap;
                 auto at = [lsel, &cs](int idx) {
                     int s = 0;
-                    if (idx >= cs[0]) { idx -= cs[0]; s = 1;
-                        if (idx >= cs[1]) { idx -= cs[1]; s = 2;
-                            if (idx >= cs[2]) { idx -= cs[2]; s = 3; } } }
+#pragma unroll
+                    for (int u = 0; u + 1 < kOwn; ++u)
+                        if (s == u && idx >= cs[u]) { idx -= cs[u]; s = u + 1; }
                     return lsel[s * kSubCap + idx];
                 };
-                wave_select_k<kCandCap / kWave>(lsel, at, cs[0] + cs[1] + cs[2] + cs[3], a.k, hist + wave * 256);
-                if ((lane & 31) == src) { c[0] = a.k; c[1] = 0; c[2] = 0; c[3] = 0; n = a.k; }
+                wave_select_k<kQCap / kWave>(lsel, at, ntot, a.k, hist + wave * 256);
+                if ((lane & 31) == src) {
+                    c[0] = a.k;
+#pragma unroll
+                    for (int s = 1; s < kOwn; ++s) c[s] = 0;
+                    n = a.k;
+                }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -964,7 +990,7 @@ void mine_rows_kernel(const MineArgs a) {
             uint64_t* out = a.glist + static_cast<size_t>(q0 + ql) * a.glist_cap;
             int off = base;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int s = 0; s < kOwn; ++s) {
                 for (int e = half; e < c[s]; e += 2)
                     if (off + e < a.glist_cap) out[off + e] = qlist[s * kSubCap + e];
                 off += c[s];
@@ -1174,6 +1200,19 @@ static int rows_slices_per_xcd(int64_t nQT, int sx_max) {
     return best;
 }
 
+// Work items of 512 queries (the row kernel with all eight waves along the queries) stage half the
+// bytes of W per flop; they are taken where padding the pool to a multiple of 512 costs no more than
+// padding it to a multiple of 256, or less than a sixteenth of the pool.  XC_MINE_ROWS=narrow or wide
+// in the environment (read at every call) overrides the rule, for A/B timing and for tests.
+static bool rows_wide_items(int64_t Zq) {
+    const char* e = getenv("XC_MINE_ROWS");
+    if (e != nullptr && e[0] == 'n') return false;
+    if (e != nullptr && e[0] == 'w') return true;
+    const int64_t pad_w = (Zq + 2 * kBN - 1) / (2 * kBN) * (2 * kBN) - Zq;
+    const int64_t pad_n = (Zq + kBN - 1) / kBN * kBN - Zq;
+    return pad_w <= pad_n || pad_w * 16 <= Zq;
+}
+
 static int plan_mine(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, MinePlan* p) {
     if (t != XC_F32 && t != XC_BF16) return XC_EDTYPE;
     if (Zq < 1 || L < 1 || d < 1 || k_h < 1 || k_h > XC_MAX_K_MINE || k_h > L) return XC_ESHAPE;
@@ -1264,13 +1303,17 @@ static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, 
             for (const void* fn : fns)
                 XC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  static_cast<int>(p.lds_tile)));
-            const void* rfns[4] = {reinterpret_cast<const void*>(&mine_rows_kernel<1>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<2>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<3>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<4>)};
-            for (const void* fn : rfns)
-                XC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                 static_cast<int>(kRowsLds)));
+            const void* rfns[8] = {reinterpret_cast<const void*>(&mine_rows_kernel<1, 2>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<2, 2>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<3, 2>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<4, 2>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<1, 1>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<2, 1>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<3, 1>),
+                                   reinterpret_cast<const void*>(&mine_rows_kernel<4, 1>)};
+            for (int i = 0; i < 8; ++i)
+                XC_HIP_CHECK(hipFuncSetAttribute(rfns[i], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 static_cast<int>(rows_lds_bytes(i < 4 ? 2 : 1))));
             if (dev >= 0 && dev < 64) attr_done_mask |= 1ull << dev;
         }
     }
@@ -1284,12 +1327,15 @@ static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, 
         const int64_t nT = hi - lo;
         const bool rows_kernel = t == XC_BF16 && a.row_bytes % kStageBytes == 0 && a.row_bytes <= 4 * kStageBytes &&
                                  !force_general_kernel();
+        // work items of 512 queries where the pool fills them about as well as items of 256
+        const bool wide = rows_kernel && rows_wide_items(Zq);
+        a.nQT = wide ? (Zq + 2 * kBN - 1) / (2 * kBN) : p.nQT;
         if (nT >= kXcds) {
             // slices per XCD: as many as the phase supports, so that few query tiles are in
             // flight per XCD and their Z rows stay in that XCD's L2
             int Sx = 8;
             while (Sx > 1 && (nT < static_cast<int64_t>(kXcds) * Sx || kXcds * Sx > slices_cap(p.kcap))) Sx >>= 1;
-            if (rows_kernel) Sx = rows_slices_per_xcd(p.nQT, Sx);
+            if (rows_kernel) Sx = rows_slices_per_xcd(a.nQT, Sx);
             a.S = kXcds * Sx;
             a.Qx = kCusPerXcd / Sx;
         } else {                                           // a few tiles: one slice per tile, plain order
@@ -1304,11 +1350,23 @@ static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, 
         const bool ktail = (a.row_bytes % kStageBytes) != 0;
         if (rows_kernel) {
             // short bf16 rows: the query tile stays in registers, only W is streamed
-            switch (a.row_bytes / kStageBytes) {
-                case 1: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<1><<<kMineGrid, kMineThreads, kRowsLds, st>>>(a))); break;
-                case 2: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<2><<<kMineGrid, kMineThreads, kRowsLds, st>>>(a))); break;
-                case 3: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<3><<<kMineGrid, kMineThreads, kRowsLds, st>>>(a))); break;
-                default: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<4><<<kMineGrid, kMineThreads, kRowsLds, st>>>(a))); break;
+            const int nk = static_cast<int>(a.row_bytes / kStageBytes);
+            if (wide) {
+                constexpr size_t lds = rows_lds_bytes(1);
+                switch (nk) {
+                    case 1: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<1, 1><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
+                    case 2: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<2, 1><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
+                    case 3: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<3, 1><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
+                    default: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<4, 1><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
+                }
+            } else {
+                constexpr size_t lds = rows_lds_bytes(2);
+                switch (nk) {
+                    case 1: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<1, 2><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
+                    case 2: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<2, 2><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
+                    case 3: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<3, 2><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
+                    default: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<4, 2><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
+                }
             }
         } else if (t == XC_BF16) {
             if (ktail) XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t, true><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));

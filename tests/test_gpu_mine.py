@@ -82,6 +82,54 @@ def test_mine_increasing_scores_worst_case_for_the_threshold(L, Zq, k, d):
     assert (ids == ids_o).all()                      # bf16 products of these values are exact: no tolerance needed
 
 
+@pytest.mark.parametrize("mode", ["narrow", "wide"])
+@pytest.mark.parametrize("Zq,L,d,k", [(300, 70000, 256, 50), (513, 9000, 192, 100), (1100, 20000, 128, 64),
+                                      (40, 3000, 64, 128)])
+def test_row_kernel_layouts_match_oracle(monkeypatch, mode, Zq, L, d, k):
+    # the kernel for short bf16 rows has two wave layouts (work items of 256 or of 512 queries) and picks one
+    # by the pool size; XC_MINE_ROWS in the environment, read at every call, forces either
+    monkeypatch.setenv("XC_MINE_ROWS", mode)
+    print("case", mode, Zq, L, d, k, flush=True)
+    _case(17, Zq, L, d, torch.bfloat16, k)
+
+
+@pytest.mark.parametrize("mode", ["narrow", "wide"])
+def test_row_kernel_layouts_worst_case_lists(monkeypatch, mode):
+    # increasing scores (every label passes, lists are cut all the time) in both layouts
+    monkeypatch.setenv("XC_MINE_ROWS", mode)
+    dev = "cuda:0"
+    L, Zq, k, d = 150000, 700, 100, 128
+    W = (torch.arange(L, dtype=torch.float32)[:, None] / 65536.0 * torch.ones(d)[None, :]).to(torch.bfloat16).to(dev)
+    Z = torch.ones((Zq, d), dtype=torch.bfloat16, device=dev)
+    Z[1::2] *= -1.0
+    ids, sc = _run(Z, W, k)
+    ids_o, sc_o = orc.mine_negatives(f64(Z), f64(W), k)
+    assert (ids == ids_o).all()
+
+
+@pytest.mark.parametrize("mode", ["narrow", "wide"])
+def test_row_kernel_layouts_warm_repeat_of_some_tiles(monkeypatch, mode):
+    # a warm search that has to repeat the full search for one 256-query tile out of three: a work item of
+    # 512 queries then holds a tile that repeats and one that keeps the result of the sweep
+    import paper_2409_20156_amd as xc
+    monkeypatch.setenv("XC_MINE_ROWS", mode)
+    dev = "cuda:0"
+    Zq, L, d, k = 700, 20000, 128, 50
+    Z = synth.make_matrix(5, synth.TAG_Z, Zq, d, torch.bfloat16, dev)
+    W = synth.make_matrix(5, synth.TAG_W, L, d, torch.bfloat16, dev)
+    ws = torch.empty(xc.mine_workspace(Zq, L, d, k, xc.XC_BF16), dtype=torch.uint8, device=dev)
+    xc.mine_negatives(Z, W, k, workspace=ws)
+    for lo, want in ((300, [0, 1, 0]), (10, [1, 0, 0]), (600, [0, 0, 1])):
+        Zp = Z.clone()
+        Zp[lo:lo + 50] = (Zp[lo:lo + 50].float() * 0.05).to(torch.bfloat16)
+        xc.mine_negatives(Z, W, k, workspace=ws)                   # thresholds of the unchanged queries
+        ids, sc = xc.mine_negatives(Zp, W, k, want_scores=True, workspace=ws, warm_margin=0.05)
+        assert _fallback_flag(ws) == 1
+        assert ws[:16].view(torch.int32).cpu().numpy()[1:4].tolist() == want
+        ids_o, sc_o = orc.mine_negatives(f64(Zp), f64(W), k)
+        check_topk(ids.cpu().numpy(), sc.cpu().numpy(), ids_o, sc_o, f64(Zp), f64(W))
+
+
 def test_mine_all_scores_equal_orders_by_id():
     dev = "cuda:0"
     W = torch.zeros((3000, 64), dtype=torch.bfloat16, device=dev)
