@@ -645,10 +645,11 @@ constexpr size_t rows_lds_bytes(int wm) {     // ring, list fills at the end of 
     return static_cast<size_t>(kRing) * wm * 64 * kStageBytes + kBN * 4 * sizeof(int) + kMineWaves * 256 * sizeof(int);
 }
 
-// XC_MINE_GENERAL=1 in the environment sends every shape through the general tile kernel (for A/B timing)
+// XC_MINE_GENERAL=1 in the environment (read at every call) sends every shape through the general tile
+// kernel, for A/B timing and for tests
 static bool force_general_kernel() {
-    static const bool v = [] { const char* e = getenv("XC_MINE_GENERAL"); return e != nullptr && e[0] == '1'; }();
-    return v;
+    const char* e = getenv("XC_MINE_GENERAL");
+    return e != nullptr && e[0] == '1';
 }
 
 // The lane number, computed where it is asked for (the compiler can neither hoist nor keep it).
@@ -677,6 +678,7 @@ __device__ __noinline__ void issue_stage_ragged(const unsigned char* W, int64_t 
 template <int NK, int WM>
 __global__ __launch_bounds__(kMineThreads, 1)
 void mine_rows_kernel(const MineArgs a) {
+    static_assert(WM == 1 || WM == 2, "wave layouts");
     constexpr int kRowTile = 64 * WM;                   // labels per tile
     constexpr int kRowStage = kRowTile * kStageBytes;   // bytes of a stage
     constexpr int kQN = (kMineWaves / WM) * 64;         // queries per work item
@@ -999,6 +1001,23 @@ void mine_rows_kernel(const MineArgs a) {
     }
 }
 
+// The instances of the row kernel: rows of 128..512 bytes in either wave layout.  (With four waves, one per
+// SIMD and 512 registers each, the queries of rows up to 1 KiB fit as well; measured at 1 KiB rows that
+// ran 15 % slower than the general kernel - no second wave covers a wave's barrier and filter time.)
+typedef void (*RowsKernelFn)(const MineArgs);
+struct RowsKernel { RowsKernelFn fn; int nk, wm; };
+static const RowsKernel kRowsKernels[] = {
+    {&mine_rows_kernel<1, 2>, 1, 2}, {&mine_rows_kernel<2, 2>, 2, 2},
+    {&mine_rows_kernel<3, 2>, 3, 2}, {&mine_rows_kernel<4, 2>, 4, 2},
+    {&mine_rows_kernel<1, 1>, 1, 1}, {&mine_rows_kernel<2, 1>, 2, 1},
+    {&mine_rows_kernel<3, 1>, 3, 1}, {&mine_rows_kernel<4, 1>, 4, 1},
+};
+static const RowsKernel* find_rows_kernel(int nk, int wm) {
+    for (const RowsKernel& k : kRowsKernels)
+        if (k.nk == nk && k.wm == wm) return &k;
+    return nullptr;
+}
+
 __global__ void mine_init_kernel(uint32_t* tau_g, int32_t* gcnt, int64_t n, uint32_t* zeros /* [64] */,
                                  const int32_t* cond) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -1303,17 +1322,10 @@ static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, 
             for (const void* fn : fns)
                 XC_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  static_cast<int>(p.lds_tile)));
-            const void* rfns[8] = {reinterpret_cast<const void*>(&mine_rows_kernel<1, 2>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<2, 2>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<3, 2>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<4, 2>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<1, 1>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<2, 1>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<3, 1>),
-                                   reinterpret_cast<const void*>(&mine_rows_kernel<4, 1>)};
-            for (int i = 0; i < 8; ++i)
-                XC_HIP_CHECK(hipFuncSetAttribute(rfns[i], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                 static_cast<int>(rows_lds_bytes(i < 4 ? 2 : 1))));
+            for (const RowsKernel& k : kRowsKernels)
+                XC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k.fn),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 static_cast<int>(rows_lds_bytes(k.wm))));
             if (dev >= 0 && dev < 64) attr_done_mask |= 1ull << dev;
         }
     }
@@ -1325,11 +1337,15 @@ static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, 
     // one phase: the tile kernel over label tiles [lo, hi), then the select
     auto phase = [&](int64_t lo, int64_t hi, const int32_t* cond, int32_t* short_flag) -> int {
         const int64_t nT = hi - lo;
-        const bool rows_kernel = t == XC_BF16 && a.row_bytes % kStageBytes == 0 && a.row_bytes <= 4 * kStageBytes &&
-                                 !force_general_kernel();
-        // work items of 512 queries where the pool fills them about as well as items of 256
-        const bool wide = rows_kernel && rows_wide_items(Zq);
-        a.nQT = wide ? (Zq + 2 * kBN - 1) / (2 * kBN) : p.nQT;
+        // bf16 rows of whole stages whose queries fit a wave's registers take the row kernel: work items of
+        // 512 queries where the pool fills them about as well as items of 256
+        const RowsKernel* rk = nullptr;
+        if (t == XC_BF16 && a.row_bytes % kStageBytes == 0 && !force_general_kernel()) {
+            const int nk = static_cast<int>(a.row_bytes / kStageBytes);
+            rk = find_rows_kernel(nk, rows_wide_items(Zq) ? 1 : 2);
+        }
+        const bool rows_kernel = rk != nullptr;
+        a.nQT = rows_kernel ? (Zq + 2 * kBN / rk->wm - 1) / (2 * kBN / rk->wm) : p.nQT;
         if (nT >= kXcds) {
             // slices per XCD: as many as the phase supports, so that few query tiles are in
             // flight per XCD and their Z rows stay in that XCD's L2
@@ -1349,25 +1365,8 @@ static int run_mine(const void* Z, const void* W, int64_t Zq, int64_t L, int d, 
         a.cond = cond;
         const bool ktail = (a.row_bytes % kStageBytes) != 0;
         if (rows_kernel) {
-            // short bf16 rows: the query tile stays in registers, only W is streamed
-            const int nk = static_cast<int>(a.row_bytes / kStageBytes);
-            if (wide) {
-                constexpr size_t lds = rows_lds_bytes(1);
-                switch (nk) {
-                    case 1: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<1, 1><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
-                    case 2: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<2, 1><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
-                    case 3: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<3, 1><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
-                    default: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<4, 1><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
-                }
-            } else {
-                constexpr size_t lds = rows_lds_bytes(2);
-                switch (nk) {
-                    case 1: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<1, 2><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
-                    case 2: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<2, 2><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
-                    case 3: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<3, 2><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
-                    default: XC_LAUNCH(K_MINE_TILE, st, (mine_rows_kernel<4, 2><<<kMineGrid, kMineThreads, lds, st>>>(a))); break;
-                }
-            }
+            // the query tile stays in registers, only W is streamed
+            XC_LAUNCH(K_MINE_TILE, st, (rk->fn<<<kMineGrid, kMineThreads, rows_lds_bytes(rk->wm), st>>>(a)));
         } else if (t == XC_BF16) {
             if (ktail) XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t, true><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));
             else XC_LAUNCH(K_MINE_TILE, st, (mine_tile_kernel<bf16_t, false><<<kMineGrid, kMineThreads, p.lds_tile, st>>>(a)));
