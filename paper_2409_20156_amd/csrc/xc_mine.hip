@@ -353,13 +353,7 @@ void mine_tile_kernel(const MineArgs a) {
             if (++ld_kb == a.nkb) { ld_kb = 0; ++ld_tile; wld += kBM * a.row_bytes; }
         };
 
-        f32x16 acc[4][2];
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-#pragma unroll
-            for (int n = 0; n < 2; ++n)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[m][n][i] = 0.0f;
+        f32x16 acc[4][2];            // (never cleared: the first k-step of a tile multiplies into zeros, see below)
 
         // ---- main loop.  At the top of a stage its data is visible in LDS, the next stage's loads
         // have been issued into the other buffer, and the fragments of its first k-step are already
@@ -381,6 +375,18 @@ void mine_tile_kernel(const MineArgs a) {
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
                     MineTraits<T>::mma(fa[sel][mt], fb[sel][nt], acc[mt][nt]);
+        };
+        // the first k-step of a tile: the accumulators start from a zero operand instead of being cleared
+        // one register at a time after the filter (128 vector moves per tile and wave)
+        auto products_first = [&](int sel) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    f32x16 c = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    MineTraits<T>::mma(fa[sel][mt], fb[sel][nt], c);
+                    acc[mt][nt] = c;
+                }
         };
         int buf_sel = 0;
         auto publish_next = [&](const unsigned char* next_buf) {
@@ -439,7 +445,7 @@ void mine_tile_kernel(const MineArgs a) {
                 buf_sel ^= 1;
                 read_frags(cur, 1, 1);
                 __builtin_amdgcn_sched_barrier(0);
-                products(0);
+                if (kb == 0) products_first(0); else products(0);
                 __builtin_amdgcn_sched_barrier(0);
                 read_frags(cur, 2, 0);
                 __builtin_amdgcn_sched_barrier(0);
@@ -514,10 +520,6 @@ void mine_tile_kernel(const MineArgs a) {
                         }
                     }
                 }
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.0f;
             };
             filter(IC<0>{});
             filter(IC<1>{});
