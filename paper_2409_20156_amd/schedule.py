@@ -67,6 +67,44 @@ class Schedule:
 
     stale_and_fresh = previous_and_fresh
 
+    def state_dict(self):
+        """Everything a later `load_state_dict` needs to go on from here with the same results: the step
+        counter, both shortlist buffers and which of them is active, built or waiting to take over, and a
+        copy of W.  A search still running on the second stream is waited for first (its takeover step is kept),
+        so the call synchronises.  The search thresholds are not part of it: the first refresh after a resume
+        starts from scratch, which returns the same shortlists as one started from earlier thresholds."""
+        if self.pending is not None:
+            self.pending[2].synchronize()
+        torch.cuda.synchronize(self.W.device)
+        return {"t": self.t, "cur": self.cur, "built": self.built, "had_previous": self.had_previous,
+                "pending": None if self.pending is None else (self.pending[0], self.pending[1]),
+                "full_repeats": int(self.full_repeats.item()),
+                "shortlist": [s.cpu().clone() for s in self.shortlist], "W": self.W.cpu().clone()}
+
+    def load_state_dict(self, sd):
+        """Back to the state `state_dict` saved (same pool, shapes and schedule parameters); W is overwritten."""
+        if tuple(sd["W"].shape) != tuple(self.W.shape) or sd["W"].dtype != self.W.dtype:
+            raise ValueError("the saved W does not fit this schedule")
+        if any(tuple(a.shape) != tuple(b.shape) for a, b in zip(sd["shortlist"], self.shortlist)):
+            raise ValueError("the saved shortlists do not fit this schedule")
+        if self.pending is not None:
+            self.pending[2].synchronize()
+        self.W.copy_(sd["W"])
+        for dst, src in zip(self.shortlist, sd["shortlist"]):
+            dst.copy_(src)
+        self.t, self.cur, self.built, self.had_previous = sd["t"], sd["cur"], sd["built"], sd["had_previous"]
+        self.full_repeats.fill_(sd["full_repeats"])
+        self.pending = None
+        if sd["pending"] is not None:
+            if self.lag == 0:
+                raise ValueError("the saved state waits for an asynchronous search; this schedule has lag 0")
+            done = torch.cuda.Event()
+            done.record(torch.cuda.current_stream())           # the buffer is complete: nothing left to wait for
+            self.pending = (sd["pending"][0], sd["pending"][1], done)
+        self.searched = False
+        self.refreshed = False
+        torch.cuda.synchronize(self.W.device)
+
     def step(self, seed: int):
         t = self.t
         self.refreshed = False

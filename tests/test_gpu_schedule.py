@@ -53,3 +53,44 @@ def test_schedule_matches_oracle(kind, lag, warm):
     assert np.allclose(overlaps, ref["overlap"], atol=1e-12)
     assert 0.0 < min(overlaps) and max(overlaps) < 1.0      # the refresh did change the lists
     check_rows_close(f64(W), W64, tol, "W after the schedule")
+
+
+@pytest.mark.parametrize("lag,warm,cut", [(0, None, 3), (2, None, 4), (0, 0.1, 4), (2, 0.0, 2)])
+def test_schedule_resumes_from_a_saved_state_bit_for_bit(lag, warm, cut):
+    """Stop after `cut` steps (with lag 2 and refreshes at 1, 3, 5 a search is then waiting to take over), save,
+    build a new schedule on other tensors, load, go on: losses and the final W equal the uninterrupted run's bits."""
+    from paper_2409_20156_amd.schedule import Schedule
+    L, d, B, pool, k_p, k_h, k_r = 4096, 64, 32, 64, 2, 8, 16
+    steps, tau_s, tau_r, lr = 8, 1, 2, 0.3
+    W0 = synth.make_matrix(12, synth.TAG_W, L, d, torch.float32, DEV)
+    Z = synth.make_matrix(12, synth.TAG_Z, pool, d, torch.float32, DEV)
+    pos = synth.zipf_positives(12, pool, L, 1.0, "uniform:1:2", k_p)
+    Z = synth.add_positive_signal(Z, W0, pos)
+    pos_t = torch.tensor(pos, device=DEV)
+    seeds = [synth.step_seed(synth.BASE_SEED, 10, t) for t in range(steps)]
+
+    def run(sch, ts):
+        losses = []
+        for t in ts:
+            losses.append(sch.step(seeds[t])["loss"].clone())
+        torch.cuda.synchronize()
+        return [float(x.item()) for x in losses]
+
+    Wa = W0.clone()
+    a = Schedule(Z, Wa, pos_t, B, k_h, k_r, tau_s, tau_r, lr, lag=lag, warm_margin=warm)
+    loss_a = run(a, range(steps))
+
+    Wb = W0.clone()
+    b = Schedule(Z, Wb, pos_t, B, k_h, k_r, tau_s, tau_r, lr, lag=lag, warm_margin=warm)
+    loss_b = run(b, range(cut))
+    sd = b.state_dict()
+    if lag == 2 and cut in (2, 4):
+        assert sd["pending"] is not None               # saved between the start of a search and its takeover
+    del b
+    Wc = torch.zeros_like(W0)                           # whatever it holds: the saved W replaces it
+    c = Schedule(Z, Wc, pos_t, B, k_h, k_r, tau_s, tau_r, lr, lag=lag, warm_margin=warm)
+    c.load_state_dict(sd)
+    assert c.t == cut
+    loss_c = run(c, range(cut, steps))
+    assert loss_b + loss_c == loss_a
+    assert torch.equal(Wc, Wa)
