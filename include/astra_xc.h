@@ -66,6 +66,10 @@ int xc_version(void);
  * Requires 1 <= k_h <= min(L, XC_MAX_K_MINE), d*sizeof(element) a multiple of 16.
  * A score that is NaN is never selected; a query with fewer than k_h finite
  * scores gets id -1 and score -inf in the remaining slots.
+ * Two environment variables, read at every call, only choose between kernels
+ * that return the same result (for A/B timing and tests): XC_MINE_GENERAL=1
+ * sends every shape through the general tile kernel; XC_MINE_ROWS=narrow or
+ * wide fixes the work-item width of the kernel for bf16 rows of 128..512 bytes.
  * ------------------------------------------------------------------------- */
 int xc_mine_workspace(int64_t Zq, int64_t L, int d, int k_h, xc_dtype t, size_t* bytes);
 int xc_mine_negatives(const void* Z, const void* W, int64_t Zq, int64_t L, int d, int k_h,
