@@ -344,3 +344,62 @@ def test_step_reduced_batch_in_full(job, kind):
         assert (_rows64(job.W, touched) == got).all()
     finally:
         job.restore(touched)
+
+
+# ------------------------------------------------------- several steps in a row ----
+@pytest.mark.parametrize("name", ["c2", "c3"])
+def test_steps_in_sequence_each_side_on_its_own_trajectory(name):
+    """Three BCE steps at full batch size, the library on its W and the oracle on its own float64 copy of the
+    generated matrix (rounded to bf16 after every step, as stored): no state passes between the two.  Per step:
+    the touched list is equal, loss and dZ within the one-step tolerance times the number of steps so far (a row
+    that came out one ulp apart feeds the next step).  At the end every row that was touched is compared:
+    norm-wise 2e-3, element-wise at most two bf16 ulps of the largest value the element held, and different at all on at most 0.6 % of
+    the elements (0.2 % per step)."""
+    import paper_2409_20156_amd as xc
+    free, _ = torch.cuda.mem_get_info()
+    wl = synth.WORKLOADS[name]
+    if free < wl.L * wl.d * 2 * 1.1 + 6e9:
+        pytest.skip("not enough device memory for %s" % name)
+    job = Job(name)
+    tol = TOL[wl.dtype]
+    W64 = f64(job.W)                                   # the generated matrix, the oracle's own copy from here on
+    Zb = job.Z[:wl.B]
+    Z64 = f64(Zb)
+    pos = job.pos
+    pos_t = torch.tensor(pos, device=DEV)
+    ever = np.zeros(wl.L, dtype=bool)
+    gsum = np.zeros(wl.L)                              # per label: sum of |d loss / d score| over all steps
+    peak = np.abs(W64).astype(np.float32)              # per element: the largest magnitude it had at any step
+    n_steps = 3
+    for t in range(n_steps):
+        neg, logq = _synthetic_negatives(wl, np.random.default_rng(300 + 10 * wl.config_id + t))
+        print("sequence", name, "step", t, flush=True)
+        out = xc.xc_step(Zb, job.W, pos_t, torch.tensor(neg, device=DEV), torch.tensor(logq, device=DEV), wl.lr)
+        torch.cuda.synchronize()
+        ref = orc.xc_step(Z64, W64, pos, neg, logq, wl.lr, storage=wl.dtype)
+        W64[ref["touched"]] = ref["W_rows"]
+        peak[ref["touched"]] = np.maximum(peak[ref["touched"]], np.abs(ref["W_rows"]).astype(np.float32))
+        ever[ref["touched"]] = True
+        for lst in ref["coef"]:
+            for l, g in lst:
+                gsum[l] += abs(g)
+        nt = int(out["n_touched"].item())
+        assert nt == len(ref["touched"]) and (out["touched"][:nt].cpu().numpy() == ref["touched"]).all()
+        loss = float(out["loss"].item())
+        assert abs(loss - ref["loss"]) <= (t + 1) * tol * abs(ref["loss"]), (t, loss, ref["loss"])
+        check_rows_close(out["dZ"].cpu().numpy(), ref["dZ"], (t + 1) * tol, "dZ of step %d" % t)
+    rows = np.where(ever)[0]
+    got, want = _rows64(job.W, rows), W64[rows]
+    diff = np.abs(got - want)
+    # the ulp of the largest value the element held on the way: a rounding that fell differently at one step
+    # stays in the element as an absolute difference, also where later updates shrink the element
+    big = np.maximum(peak[rows].astype(np.float64), np.abs(got))
+    _, e = np.frexp(big)
+    ulp = np.ldexp(1.0, np.maximum(e, -125) - 8)
+    assert (np.linalg.norm(diff, axis=1) / np.maximum(np.linalg.norm(want, axis=1), 1e-30)).max() <= 2e-3
+    # (plus the float32 error of the operands and of a gradient sum whose terms cancel, as in check_bf16_rows)
+    allowed = 2.0000001 * ulp + 2.0 ** -17 * big + (2e-6 * wl.lr * gsum[rows] * np.abs(Z64).max())[:, None]
+    assert (diff <= allowed).all(), float((diff / allowed).max())
+    assert (diff > 0).mean() <= 0.002 * n_steps, float((diff > 0).mean())
+    others = np.where(~ever)[0][:4000]
+    assert (_rows64(job.W, others) == W64[others]).all()           # never touched: the generated bits
