@@ -347,14 +347,16 @@ def test_step_reduced_batch_in_full(job, kind):
 
 
 # ------------------------------------------------------- several steps in a row ----
-@pytest.mark.parametrize("name", ["c2", "c3"])
-def test_steps_in_sequence_each_side_on_its_own_trajectory(name):
-    """Three BCE steps at full batch size, the library on its W and the oracle on its own float64 copy of the
-    generated matrix (rounded to bf16 after every step, as stored): no state passes between the two.  Per step:
+@pytest.mark.parametrize("name,nb", [("c2", None), ("c3", None), ("c5", SUB_BATCH)])
+def test_steps_in_sequence_each_side_on_its_own_trajectory(name, nb):
+    """Three BCE steps, the library on its W and the oracle on its own float64 copy of the generated rows
+    (rounded to bf16 after every step, as stored): no state passes between the two.  c2 and c3 at full batch
+    size with the whole matrix on the oracle's side; c5 (rows updated inside the gather, wide sort keys) with a
+    reduced batch and, for the oracle, the renumbered sub-problem of the rows that the three steps use.  Per step:
     the touched list is equal, loss and dZ within the one-step tolerance times the number of steps so far (a row
     that came out one ulp apart feeds the next step).  At the end every row that was touched is compared:
-    norm-wise 2e-3, element-wise at most two bf16 ulps of the largest value the element held, and different at all on at most 0.6 % of
-    the elements (0.2 % per step)."""
+    norm-wise 2e-3, element-wise at most two bf16 ulps of the largest value the element held, and different at all
+    on at most 0.6 % of the elements (0.2 % per step)."""
     import paper_2409_20156_amd as xc
     free, _ = torch.cuda.mem_get_info()
     wl = synth.WORKLOADS[name]
@@ -362,21 +364,38 @@ def test_steps_in_sequence_each_side_on_its_own_trajectory(name):
         pytest.skip("not enough device memory for %s" % name)
     job = Job(name)
     tol = TOL[wl.dtype]
-    W64 = f64(job.W)                                   # the generated matrix, the oracle's own copy from here on
-    Zb = job.Z[:wl.B]
-    Z64 = f64(Zb)
-    pos = job.pos
-    pos_t = torch.tensor(pos, device=DEV)
-    ever = np.zeros(wl.L, dtype=bool)
-    gsum = np.zeros(wl.L)                              # per label: sum of |d loss / d score| over all steps
-    peak = np.abs(W64).astype(np.float32)              # per element: the largest magnitude it had at any step
+    B = nb if nb is not None else wl.B
     n_steps = 3
+    Zb = job.Z[:B]
+    Z64 = f64(Zb)
+    pos = job.pos[:B]
+    negs = [_synthetic_negatives(wl, np.random.default_rng(300 + 10 * wl.config_id + t)) for t in range(n_steps)]
+    negs = [(ng[:B], lq[:B]) for ng, lq in negs]
+    if nb is None:
+        ids_of = np.arange(wl.L)                       # the oracle holds every row
+        W64 = f64(job.W)
+        pos_o, negs_o = pos, [ng for ng, _ in negs]
+    else:
+        allids = np.concatenate([pos.reshape(-1)] + [ng.reshape(-1) for ng, _ in negs]).astype(np.int64)
+        ids_of = np.unique(allids[(allids >= 0) & (allids < wl.L)])
+        W64 = job.original_rows(ids_of)
+
+        def remap(a):
+            a = a.astype(np.int64)
+            inside = (a >= 0) & (a < wl.L)
+            return np.where(inside, np.searchsorted(ids_of, np.clip(a, 0, wl.L - 1)), -1).astype(np.int32)
+        pos_o, negs_o = remap(pos), [remap(ng) for ng, _ in negs]
+    U = len(ids_of)
+    pos_t = torch.tensor(pos, device=DEV)
+    ever = np.zeros(U, dtype=bool)
+    gsum = np.zeros(U)                                 # per label: sum of |d loss / d score| over all steps
+    peak = np.abs(W64).astype(np.float32)              # per element: the largest magnitude it had at any step
     for t in range(n_steps):
-        neg, logq = _synthetic_negatives(wl, np.random.default_rng(300 + 10 * wl.config_id + t))
+        neg, logq = negs[t]
         print("sequence", name, "step", t, flush=True)
         out = xc.xc_step(Zb, job.W, pos_t, torch.tensor(neg, device=DEV), torch.tensor(logq, device=DEV), wl.lr)
         torch.cuda.synchronize()
-        ref = orc.xc_step(Z64, W64, pos, neg, logq, wl.lr, storage=wl.dtype)
+        ref = orc.xc_step(Z64, W64, pos_o, negs_o[t], logq, wl.lr, storage=wl.dtype)
         W64[ref["touched"]] = ref["W_rows"]
         peak[ref["touched"]] = np.maximum(peak[ref["touched"]], np.abs(ref["W_rows"]).astype(np.float32))
         ever[ref["touched"]] = True
@@ -384,12 +403,12 @@ def test_steps_in_sequence_each_side_on_its_own_trajectory(name):
             for l, g in lst:
                 gsum[l] += abs(g)
         nt = int(out["n_touched"].item())
-        assert nt == len(ref["touched"]) and (out["touched"][:nt].cpu().numpy() == ref["touched"]).all()
+        assert nt == len(ref["touched"]) and (out["touched"][:nt].cpu().numpy() == ids_of[ref["touched"]]).all()
         loss = float(out["loss"].item())
         assert abs(loss - ref["loss"]) <= (t + 1) * tol * abs(ref["loss"]), (t, loss, ref["loss"])
         check_rows_close(out["dZ"].cpu().numpy(), ref["dZ"], (t + 1) * tol, "dZ of step %d" % t)
     rows = np.where(ever)[0]
-    got, want = _rows64(job.W, rows), W64[rows]
+    got, want = _rows64(job.W, ids_of[rows]), W64[rows]
     diff = np.abs(got - want)
     # the ulp of the largest value the element held on the way: a rounding that fell differently at one step
     # stays in the element as an absolute difference, also where later updates shrink the element
@@ -401,5 +420,8 @@ def test_steps_in_sequence_each_side_on_its_own_trajectory(name):
     allowed = 2.0000001 * ulp + 2.0 ** -17 * big + (2e-6 * wl.lr * gsum[rows] * np.abs(Z64).max())[:, None]
     assert (diff <= allowed).all(), float((diff / allowed).max())
     assert (diff > 0).mean() <= 0.002 * n_steps, float((diff > 0).mean())
-    others = np.where(~ever)[0][:4000]
-    assert (_rows64(job.W, others) == W64[others]).all()           # never touched: the generated bits
+    if nb is None:
+        others = np.where(~ever)[0][:4000]
+    else:
+        others = np.setdiff1d(np.random.default_rng(7).integers(0, wl.L, size=4000), ids_of)
+    assert (_rows64(job.W, others) == job.original_rows(others)).all()   # never touched: the generated bits
